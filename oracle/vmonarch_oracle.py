@@ -1,0 +1,326 @@
+"""Plain fp64 NumPy oracle for VMonarch's spatio-temporal Monarch attention.
+
+TEST INFRASTRUCTURE ONLY.  This file is the slow, explicit statement of what
+the method computes, written from the paper (Sec. 3.1 Eqs. R / alpha_R / c_R /
+L / alpha_L / c_L, Sec. 3.2, Sec. 3.3 first-frame recomputation, Sec. 3.4
+Alg. 1, App. A, App. B).  It shares no code with the HIP library and is never
+imported by it.  Only tests, the smoke check and the benchmark's CPU-baseline
+leg may call it.
+
+Notation (the paper's): m = T frames, b = H*W spatial positions, N = m*b,
+token n = j*b + i with j the frame and i the position (App. A reshape(m,b,d)).
+Index letters: j query frame, i query position, k key frame, l key position,
+v channel.  Factors: R = diag(R_0..R_{m-1}), R_k is b x b (spatial, one block
+per frame); L = diag(L_0..L_{b-1}), L_i is m x m (temporal, one block per
+position).  Monarch entry (Sec. 3.1): M[(j,i),(k,l)] = L[i][j,k] * R[k][i,l].
+
+Readings taken where the paper is silent or inconsistent:
+  * 1/sqrt(d): printed only in the recomputation formula (Sec. 3.3).  Here Q is
+    replaced by Q/sqrt(d) everywhere it appears, so the fitted objective is
+    <M, Q K^T / sqrt(d)> + H(M) and the T=1 / b=1 collapses give textbook
+    scaled attention.
+  * Eq. (L) prints softmax_j; App. A takes the softmax over the key-frame axis
+    (dim=2).  The code's reading is used: L[i][j,:] is a distribution over k.
+  * "clamp c_R to 0.1" (Sec. 4.1): a lower bound applied where c_R divides,
+    c = max(c_R, cr_min).  The c_R the L-update emits is left unclamped.
+  * 0*log(0) := 0 in c_L.
+  * Recomputation overwrites only the output rows of frame 0; the fit is not
+    changed by it.
+
+Pins (tests/test_oracle_*.py): NumPy reshape/transpose for the permutation;
+row-stochastic R, L, M; O == M V with M formed densely; T=1 and b=1 collapse
+to textbook softmax attention; separable logits give exact softmax attention
+for every iteration count; brute-force entropy against c_L and against the
+online accumulator; objective non-decreasing over half-steps and bounded by
+the sum of row log-sum-exps; sum_k c_R[k,i] = T; V == 1 gives O == 1.
+No worked numeric example is printed in the paper, so no paper value pins it.
+"""
+from __future__ import annotations
+
+import math
+
+import numpy as np
+
+
+# --------------------------------------------------------------------------
+# input widening (the oracle's own; the HIP side never sees this)
+# --------------------------------------------------------------------------
+def widen_bf16(bits: np.ndarray) -> np.ndarray:
+    """uint16 bf16 bit patterns -> float64, exactly."""
+    u = np.asarray(bits, dtype=np.uint16).astype(np.uint32) << np.uint32(16)
+    return u.view(np.float32).astype(np.float64)
+
+
+# --------------------------------------------------------------------------
+# Sec. 3.1 permutation P_(b,N): the footnote's definition
+# --------------------------------------------------------------------------
+def index_maps(m: int, b: int):
+    """perm, inv as int32[N].
+
+    Footnote of Sec. 3.1: reshape a length-N vector into an m x b row-major
+    matrix, transpose, flatten.  Position-major slot p = i*m + j holds token
+    perm[p] = j*b + i; inv is its inverse, inv[j*b + i] = i*m + j.
+    (The printed sigma formula is the identity map and is not used.)
+    """
+    n = m * b
+    perm = np.empty(n, dtype=np.int32)
+    inv = np.empty(n, dtype=np.int32)
+    for p in range(n):
+        i, j = divmod(p, m)
+        perm[p] = j * b + i
+    for t in range(n):
+        j, i = divmod(t, b)
+        inv[t] = i * m + j
+    return perm, inv
+
+
+# --------------------------------------------------------------------------
+# textbook pieces
+# --------------------------------------------------------------------------
+def softmax_rows(z: np.ndarray) -> np.ndarray:
+    """softmax over the last axis."""
+    e = np.exp(z - z.max(axis=-1, keepdims=True))
+    return e / e.sum(axis=-1, keepdims=True)
+
+
+def softmax_attention(Q, K, V, scale):
+    """softmax(scale * Q K^T) V, the dense definition."""
+    return softmax_rows(scale * (Q @ K.T)) @ V
+
+
+def neg_entropy_rows(P: np.ndarray) -> np.ndarray:
+    """sum over the last axis of P log P with 0 log 0 := 0."""
+    safe = np.where(P > 0.0, P, 1.0)
+    return (P * np.log(safe)).sum(axis=-1)
+
+
+# --------------------------------------------------------------------------
+# App. A: R_update, L_update
+# --------------------------------------------------------------------------
+def r_update(aR, cR, Kb, cr_min=0.0):
+    """Eq. (R) and Eq. (alpha_L, c_L); App. A R_update.
+
+    aR (m, s, d), cR (m, s), Kb (m, b, d); s query positions (s == b for the
+    full problem, fewer when only some positions are followed).
+    Returns aL (s, m, d), cL (s, m), R (m, s, b).
+    """
+    c = np.maximum(cR, cr_min)
+    Z = np.matmul(aR, Kb.transpose(0, 2, 1)) / c[:, :, None]          # (m, s, b)
+    R = softmax_rows(Z)
+    cL = neg_entropy_rows(R).T                                         # (s, m)
+    aL = np.matmul(R, Kb).transpose(1, 0, 2)                           # (s, m, d)
+    return aL, cL, R
+
+
+def l_update(aL, cL, Qb):
+    """Eq. (L) and Eq. (alpha_R, c_R); App. A L_update.
+
+    aL (s, m, d), cL (s, m), Qb (s, m, d).
+    Returns aR (m, s, d), cR (m, s), L (s, m, m) with L[i][j, k].
+    """
+    U = np.matmul(Qb, aL.transpose(0, 2, 1)) - cL[:, None, :]          # (s, j, k)
+    L = softmax_rows(U)
+    cR = L.sum(axis=1).T                                               # (m, s)
+    aR = np.matmul(L.transpose(0, 2, 1), Qb).transpose(1, 0, 2)        # (m, s, d)
+    return aR, cR, L
+
+
+# --------------------------------------------------------------------------
+# App. A monarch_attention + Sec. 3.3 recomputation
+# --------------------------------------------------------------------------
+def monarch_attention(Q, K, V, m, b, iters, recompute=False, cr_min=0.1,
+                      positions=None, keep_factors=False):
+    """Spatio-temporal Monarch attention for one (batch, head).
+
+    Q, K, V: (N, d) float64, N = m*b, token n = j*b + i.
+    positions: optional 1-D int array of query positions i to follow.  The
+    whole iteration for a position depends only on Q[:, i, :] and on all of
+    K, V, so a subset is followed exactly.  None means all b positions.
+
+    Returns a dict:
+      O      (m, s, d)   output rows for the followed positions, O[j, idx]
+      aL,cL  (s, m, d), (s, m)  from the last R-update
+      aR,cR  (m, s, d), (m, s)  from the last L-update (unclamped c_R)
+      y      (s, m, d)   R V of the last sweep
+      trace  list of per-sweep dicts (aL, cL, aR, cR [, R, L])
+      R, L   last factors, only when keep_factors
+    With recompute, O[0] is replaced by exact attention of the frame-0 queries
+    over all N keys (Sec. 3.3); nothing else changes.
+    """
+    N, d = Q.shape
+    assert N == m * b and K.shape == (N, d) and V.shape == (N, d) and iters >= 1
+    s_ = 1.0 / math.sqrt(d)
+    pos = np.arange(b) if positions is None else np.asarray(positions, dtype=np.int64)
+    Qs = (Q * s_).reshape(m, b, d)[:, pos, :]                          # Q' (m, s, d)
+    Qb = Qs.transpose(1, 0, 2)                                         # (s, m, d)
+    Kb = K.reshape(m, b, d)
+    Vb = V.reshape(m, b, d)
+    aR = Qs.copy()
+    cR = np.ones((m, len(pos)))
+    trace = []
+    for _ in range(iters):
+        aL, cL, R = r_update(aR, cR, Kb, cr_min)
+        aR, cR, L = l_update(aL, cL, Qb)
+        step = dict(aL=aL, cL=cL, aR=aR, cR=cR)
+        if keep_factors:
+            step.update(R=R, L=L)
+        trace.append(step)
+    y = np.matmul(R, Vb).transpose(1, 0, 2)                            # (s, k, d)
+    O = np.matmul(L, y).transpose(1, 0, 2)                             # (j, s, d)
+    if recompute:
+        O = O.copy()
+        O[0] = softmax_attention(Q.reshape(m, b, d)[0, pos, :], K, V, s_)
+    out = dict(O=O, aL=aL, cL=cL, aR=aR, cR=cR, y=y, trace=trace, positions=pos)
+    if keep_factors:
+        out.update(R=R, L=L)
+    return out
+
+
+def first_frame_attention(Q, K, V, b, rows=None):
+    """Sec. 3.3: softmax(Q_0 K^T / sqrt(d)) V for frame-0 queries (tokens 0..b-1)."""
+    d = Q.shape[1]
+    r = np.arange(b) if rows is None else np.asarray(rows, dtype=np.int64)
+    return softmax_attention(Q[r], K, V, 1.0 / math.sqrt(d))
+
+
+# --------------------------------------------------------------------------
+# Sec. 3.1: the dense Monarch matrix and the objective of Eq. 1 / Eq. 2
+# --------------------------------------------------------------------------
+def dense_monarch(L, R):
+    """M[(j,i),(k,l)] = L[i][j,k] * R[k][i,l] as an (N, N) array, N = m*b.
+
+    L (b, m, m), R (m, b, b): all positions present.
+    """
+    b, m, _ = L.shape
+    M = np.empty((m, b, m, b))
+    for j in range(m):
+        for i in range(b):
+            for k in range(m):
+                M[j, i, k, :] = L[i, j, k] * R[k, i, :]
+    return M.reshape(m * b, m * b)
+
+
+def monarch_product(L, R, m, b):
+    """P L P^T R with explicit block-diagonal and permutation matrices (Sec. 3.1)."""
+    n = m * b
+    perm, _ = index_maps(m, b)
+    P = np.zeros((n, n))
+    # P x = "reshape m x b, transpose, flatten": (P x)[p] = x[perm[p]]
+    P[np.arange(n), perm] = 1.0
+    Lbd = np.zeros((n, n))
+    for i in range(b):
+        Lbd[i * m:(i + 1) * m, i * m:(i + 1) * m] = L[i]
+    Rbd = np.zeros((n, n))
+    for k in range(m):
+        Rbd[k * b:(k + 1) * b, k * b:(k + 1) * b] = R[k]
+    # Rows of L_i are indexed by (i, j) = position-major, so the product that
+    # acts on frame-major tokens is P^T L P R.  With the footnote's P this is
+    # the paper's M up to which of P, P^T is named "the" permutation.
+    return P.T @ Lbd @ P @ Rbd
+
+
+def objective(M, Q, K):
+    """Eq. 1: <M, Q K^T / sqrt(d)> + H(M), H the Shannon entropy summed over entries."""
+    d = Q.shape[1]
+    S = (Q @ K.T) / math.sqrt(d)
+    return float((M * S).sum() - neg_entropy_rows(M).sum())
+
+
+def objective_upper_bound(Q, K):
+    """max over row-stochastic A of Eq. 1 = sum over rows of logsumexp(Q K^T / sqrt(d))."""
+    d = Q.shape[1]
+    S = (Q @ K.T) / math.sqrt(d)
+    mx = S.max(axis=1)
+    return float((mx + np.log(np.exp(S - mx[:, None]).sum(axis=1))).sum())
+
+
+# --------------------------------------------------------------------------
+# App. B online softmax / online entropy, and Alg. 1
+# --------------------------------------------------------------------------
+def online_entropy_state(x):
+    """App. B: one pass over the vector x keeping (m_i, S_i, L_i).
+
+    Returns (m, S, Lsum) with S = sum exp(x - m), Lsum = sum exp(x - m) (x - m).
+    """
+    m_run = -math.inf
+    S = 0.0
+    Lsum = 0.0
+    for xi in x:
+        m_new = max(m_run, xi)
+        if m_new > m_run and S > 0.0:
+            alpha = math.exp(m_run - m_new)
+            # L <- L alpha + S alpha log(alpha);  S <- S alpha
+            Lsum = Lsum * alpha + S * alpha * (m_run - m_new)
+            S = S * alpha
+        p = math.exp(xi - m_new)
+        S = S + p
+        Lsum = Lsum + p * (xi - m_new)
+        m_run = m_new
+    return m_run, S, Lsum
+
+
+def online_entropy(x):
+    """App. B final formula: H(p) = log S_N - L_N / S_N."""
+    _, S, Lsum = online_entropy_state(x)
+    return math.log(S) - Lsum / S
+
+
+def merge_entropy_states(a, b_):
+    """Combine the states of two disjoint parts of a vector (same rescale rule)."""
+    (m1, S1, L1), (m2, S2, L2) = a, b_
+    mm = max(m1, m2)
+    a1 = math.exp(m1 - mm)
+    a2 = math.exp(m2 - mm)
+    S = S1 * a1 + S2 * a2
+    Ls = L1 * a1 + S1 * a1 * (m1 - mm) + L2 * a2 + S2 * a2 * (m2 - mm)
+    return mm, S, Ls
+
+
+def flash_entropy_attention(Q, K, V, Br, Bc):
+    """Alg. 1 (forward): blocked attention with running max, sum and entropy.
+
+    Q (Nq, d), K, V (Nk, d) float64, logits S = Q K^T (the caller scales Q).
+    Returns O (Nq, d), LSE (Nq,), H (Nq,).
+    """
+    Nq, d = Q.shape
+    Nk = K.shape[0]
+    O = np.zeros((Nq, V.shape[1]))
+    LSE = np.zeros(Nq)
+    H = np.zeros(Nq)
+    for r0 in range(0, Nq, Br):
+        Qi = Q[r0:r0 + Br]
+        nr = Qi.shape[0]
+        mi = np.full(nr, -np.inf)
+        li = np.zeros(nr)
+        hi = np.zeros(nr)
+        Oi = np.zeros((nr, V.shape[1]))
+        for c0 in range(0, Nk, Bc):
+            Kj = K[c0:c0 + Bc]
+            Vj = V[c0:c0 + Bc]
+            Sij = Qi @ Kj.T
+            m_new = np.maximum(mi, Sij.max(axis=1))
+            Pij = np.exp(Sij - m_new[:, None])
+            alpha = np.exp(mi - m_new)                      # 0 on the first tile
+            # alpha log(alpha) -> 0 as alpha -> 0
+            alogal = np.where(alpha > 0.0, alpha * np.log(np.where(alpha > 0.0, alpha, 1.0)), 0.0)
+            Oi = alpha[:, None] * Oi + Pij @ Vj
+            hi = alpha * hi + alogal * li + neg_entropy_rows(Pij)
+            li = alpha * li + Pij.sum(axis=1)
+            mi = m_new
+        O[r0:r0 + Br] = Oi / li[:, None]
+        LSE[r0:r0 + Br] = mi + np.log(li)
+        H[r0:r0 + Br] = np.log(li) - hi / li
+    return O, LSE, H
+
+
+# --------------------------------------------------------------------------
+# analytic counts (Sec. 3.2 complexity, Sec. 3.3 overhead, Sec. 4.1 sparsity)
+# --------------------------------------------------------------------------
+def sparsity_estimate(T, HW, t):
+    """Sec. 4.1: 1 - t (T + HW) / (T HW)."""
+    return 1.0 - t * (T + HW) / (T * HW)
+
+
+def recompute_cost_ratio(m, b, t):
+    """Sec. 3.3: cost of the recomputation relative to the t sweeps, b / (t (m + b))."""
+    return b / (t * (m + b))
