@@ -1,0 +1,151 @@
+/*
+ * vmonarch.h -- C ABI of the MI355X (gfx950) spatio-temporal Monarch attention library.
+ *
+ * The method is VMonarch's attention (paper Sec. 3): N = T*Hs*Ws video tokens are viewed
+ * as m = T frames of b = Hs*Ws spatial positions, token n = j*b + i (frame j, position i;
+ * the reshape(m, b, d) of App. A).  softmax(Q K^T / sqrt(d)) is replaced by a Monarch
+ * matrix M[(j,i),(k,l)] = L[i][j,k] * R[k][i,l] (Sec. 3.1) whose factors are fitted by
+ * `iters` sweeps of the closed-form alternating updates (Eqs. R, alpha_R/c_R, L,
+ * alpha_L/c_L; App. A) and applied to V; optionally the rows of frame 0 are recomputed
+ * with exact attention (Sec. 3.3).
+ *
+ * Conventions shared by every entry point
+ *   - All tensor pointers are DEVICE pointers unless a parameter says "host".
+ *   - Token tensors (q, k, v, out, aR, aL, y) are contiguous [B][heads][T][b][d]
+ *     (= [B][heads][N][d]); per-token scalars (cR, cL) are float32 [B][heads][T][b].
+ *     Note aL and cL are stored frame-major like everything else; "position-major"
+ *     (App. A's transposes) is only the order in which the L-update walks them.
+ *   - Entry points without suffix take bfloat16 token tensors; `_f32` twins take float32.
+ *     Scalars c_R, c_L are float32 in both.  Accumulation is float32 everywhere.
+ *   - `stream` is a hipStream_t passed as void* (NULL = the null stream).  Calls only
+ *     enqueue work; they never synchronise the host.
+ *   - The library never frees or retains caller memory.  Outputs must not alias inputs.
+ *   - Return value: 0 on success, a negative VMONARCH_ERR_* otherwise; nothing is
+ *     launched when validation fails.  vmonarch_last_error() describes the last failure
+ *     of the calling thread.  No exception crosses this boundary.
+ *   - d <= 256 for every entry point.  bf16 with d == 128 and T <= 128 runs on the MFMA
+ *     kernels; other shapes run on slower plain-ALU kernels with the same results.
+ */
+#ifndef VMONARCH_H_
+#define VMONARCH_H_
+
+#include <stddef.h>
+#include <stdint.h>
+
+#ifdef __cplusplus
+extern "C" {
+#endif
+
+#define VMONARCH_OK 0
+#define VMONARCH_ERR_INVALID_ARG (-1) /* null pointer, non-positive size, iters < 1 */
+#define VMONARCH_ERR_UNSUPPORTED (-2) /* d > 256, or a size whose index does not fit */
+#define VMONARCH_ERR_WORKSPACE (-3)   /* caller workspace too small / allocation failed */
+#define VMONARCH_ERR_HIP (-4)         /* a HIP runtime call failed */
+
+/* How the R-update obtains c_L = sum_l R log R (Eq. alpha_L/c_L). */
+#define VMONARCH_ENTROPY_ONLINE 0   /* Alg. 1 / App. B: third running statistic h beside (m, l) */
+#define VMONARCH_ENTROPY_IDENTITY 1 /* c_L = (aR . alpha_L) * scale - logsumexp, from the outputs */
+
+/* Library version: major*10000 + minor*100 + patch. */
+int vmonarch_version(void);
+
+/* Text of the calling thread's last error ("" if none).  Pointer stays valid until the
+ * thread's next failing call. */
+const char* vmonarch_last_error(void);
+
+/* Lower bound applied to c_R where it divides the logits (Sec. 4.1 "clamp c_R to 0.1").
+ * Default 0.1; 0 disables.  Process-wide; affects vmonarch_attention[_f32] only. */
+int vmonarch_set_cr_min(float cr_min);
+float vmonarch_get_cr_min(void);
+
+/* Selects VMONARCH_ENTROPY_* for the bf16 MFMA R-update (default ONLINE).  Process-wide. */
+int vmonarch_set_entropy_mode(int mode);
+int vmonarch_get_entropy_mode(void);
+
+/* Bytes of device scratch vmonarch_attention[_f32] needs for these sizes
+ * (elem_bytes = 2 for bf16, 4 for f32).  0 on invalid sizes. */
+size_t vmonarch_workspace_bytes(int B, int heads, int T, int Hs, int Ws, int d, int iters,
+                                int recompute, int elem_bytes);
+
+/* Hands the library a caller-owned device buffer to use as scratch (256-byte aligned).
+ * Passing NULL/0 returns to the library-owned arena, which grows on demand with hipMalloc
+ * (once per size increase, synchronising) and is released by vmonarch_shutdown(). */
+int vmonarch_set_workspace(void* dev_ptr, size_t bytes);
+int vmonarch_shutdown(void);
+
+/*
+ * Whole path (Eq. 5: O = MonarchAttention(Q, K, V; m = T, b = Hs*Ws, t = iters), then
+ * Sec. 3.3 if recompute != 0).  q, k, v, out: [B][heads][N][d].  1/sqrt(d) multiplies Q
+ * everywhere Q enters (fit and recomputation alike).
+ */
+int vmonarch_attention(const void* q, const void* k, const void* v, void* out, int B, int heads,
+                       int T, int Hs, int Ws, int d, int iters, int recompute, void* stream);
+int vmonarch_attention_f32(const void* q, const void* k, const void* v, void* out, int B, int heads,
+                           int T, int Hs, int Ws, int d, int iters, int recompute, void* stream);
+
+/*
+ * R-update, the intra-frame (spatial) factor (Eq. R with Eq. alpha_L/c_L; App. A R_update;
+ * computed as one blocked softmax pass with running max, sum and entropy, Alg. 1).
+ * For every frame k and query position i:
+ *     z[l]      = row_scale * (aR[k,i,:] . K[k,l,:]) / max(cR[k,i], cr_min)
+ *     R[k,i,:]  = softmax_l z                      (never stored)
+ *     aL[k,i,:] = sum_l R[k,i,l] K[k,l,:]          cL[k,i] = sum_l R[k,i,l] log R[k,i,l]
+ *     y[k,i,:]  = sum_l R[k,i,l] V[k,l,:]          (only if v and y_out are non-NULL)
+ * cR == NULL means all ones (the first sweep, where aR is Q itself).
+ */
+int vmonarch_r_update(const void* aR, const float* cR, const void* k, const void* v, void* aL_out,
+                      float* cL_out, void* y_out, int B, int heads, int T, int Hs, int Ws, int d,
+                      float row_scale, float cr_min, void* stream);
+int vmonarch_r_update_f32(const void* aR, const float* cR, const void* k, const void* v,
+                          void* aL_out, float* cL_out, void* y_out, int B, int heads, int T, int Hs,
+                          int Ws, int d, float row_scale, float cr_min, void* stream);
+
+/*
+ * L-update, the inter-frame (temporal) factor (Eq. L with Eq. alpha_R/c_R; App. A
+ * L_update), walking the frame-major tensors with stride b*d (the permutation P of
+ * Sec. 3.1 is applied as addressing, never as a copy).  For every position i:
+ *     L[i][j,:]  = softmax_k ( q_scale * (Q[j,i,:] . aL[k,i,:]) - cL[k,i] )   (never stored)
+ *   if y == NULL (fitting sweep):
+ *     aR_out[k,i,:] = sum_j L[i][j,k] Q[j,i,:]  (unscaled Q)     cR_out[k,i] = sum_j L[i][j,k]
+ *   else (last sweep, the apply-to-V of App. A):
+ *     out[j,i,:] = sum_k L[i][j,k] y[k,i,:]
+ * Exactly one of {aR_out and cR_out} / {y and out} must be given.
+ */
+int vmonarch_l_update(const void* q, const void* aL, const float* cL, const void* y, void* aR_out,
+                      float* cR_out, void* out, int B, int heads, int T, int Hs, int Ws, int d,
+                      float q_scale, void* stream);
+int vmonarch_l_update_f32(const void* q, const void* aL, const float* cL, const void* y,
+                          void* aR_out, float* cR_out, void* out, int B, int heads, int T, int Hs,
+                          int Ws, int d, float q_scale, void* stream);
+
+/*
+ * First-frame recomputation (Sec. 3.3): out[0:b] = softmax(Q[0:b] K^T / sqrt(d)) V over all
+ * N keys, per (batch, head).  Only rows 0..b-1 of each head of `out` are written.
+ * The bf16 MFMA path splits the keys over several workgroups and merges the partial
+ * results; it uses the workspace (see vmonarch_workspace_bytes with recompute != 0).
+ */
+int vmonarch_first_frame_attention(const void* q, const void* k, const void* v, void* out, int B,
+                                   int heads, int T, int Hs, int Ws, int d, void* stream);
+int vmonarch_first_frame_attention_f32(const void* q, const void* k, const void* v, void* out,
+                                       int B, int heads, int T, int Hs, int Ws, int d, void* stream);
+
+/*
+ * Permutation P_(b,N) of Sec. 3.1 (its footnote: reshape to m x b, transpose, flatten).
+ * perm, inv: HOST int32[N]; position-major slot p = i*T + j holds token perm[p] = j*b + i,
+ * and inv[j*b + i] = i*T + j.
+ */
+int vmonarch_index_maps(int T, int Hs, int Ws, int32_t* perm_host, int32_t* inv_host);
+
+/*
+ * Applies that permutation to token rows as a stand-alone copy (the fused path never
+ * calls it; it exists to check the index maps on the device and to measure the HBM rate
+ * of the strided walk).  in, out: [B][heads][N][row_bytes]; to_position_major != 0 writes
+ * out[i*T + j] = in[j*b + i], otherwise out[j*b + i] = in[i*T + j].  row_bytes % 4 == 0.
+ */
+int vmonarch_permute_tokens(const void* in, void* out, int B, int heads, int T, int Hs, int Ws,
+                            int row_bytes, int to_position_major, void* stream);
+
+#ifdef __cplusplus
+}
+#endif
+#endif /* VMONARCH_H_ */

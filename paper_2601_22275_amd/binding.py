@@ -1,0 +1,190 @@
+"""Thin ctypes binding of libvmonarch.so (argument marshalling only).
+
+Every function takes torch CUDA tensors for device memory, hands their raw
+pointers and the current HIP stream to the C ABI declared in
+``include/vmonarch.h`` and raises ``VMonarchError`` on a non-zero return code.
+No arithmetic of the method happens on the Python side, and there is no
+fallback: if the shared library has not been built, importing this module's
+library handle raises.
+"""
+from __future__ import annotations
+
+import ctypes
+import os
+from ctypes import c_char_p, c_float, c_int, c_size_t, c_void_p
+
+import torch
+
+_HERE = os.path.dirname(os.path.abspath(__file__))
+LIB_PATH = os.path.join(_HERE, "libvmonarch.so")
+
+ENTROPY_ONLINE = 0
+ENTROPY_IDENTITY = 1
+
+EXPORTS = [
+    "vmonarch_version", "vmonarch_last_error", "vmonarch_set_cr_min", "vmonarch_get_cr_min",
+    "vmonarch_set_entropy_mode", "vmonarch_get_entropy_mode", "vmonarch_workspace_bytes",
+    "vmonarch_set_workspace", "vmonarch_shutdown", "vmonarch_attention", "vmonarch_attention_f32",
+    "vmonarch_r_update", "vmonarch_r_update_f32", "vmonarch_l_update", "vmonarch_l_update_f32",
+    "vmonarch_first_frame_attention", "vmonarch_first_frame_attention_f32", "vmonarch_index_maps",
+    "vmonarch_permute_tokens",
+]
+
+
+class VMonarchError(RuntimeError):
+    pass
+
+
+_lib = None
+
+
+def lib() -> ctypes.CDLL:
+    """The loaded library; raises if it has not been built (no fallback exists)."""
+    global _lib
+    if _lib is None:
+        if not os.path.exists(LIB_PATH):
+            raise VMonarchError(f"{LIB_PATH} is missing: run `python -m paper_2601_22275_amd.build` "
+                                "(or __graft_entry__.build()) first")
+        L = ctypes.CDLL(LIB_PATH)
+        dims = [c_int] * 6
+        L.vmonarch_version.restype = c_int
+        L.vmonarch_last_error.restype = c_char_p
+        L.vmonarch_set_cr_min.argtypes = [c_float]
+        L.vmonarch_get_cr_min.restype = c_float
+        L.vmonarch_set_entropy_mode.argtypes = [c_int]
+        L.vmonarch_workspace_bytes.restype = c_size_t
+        L.vmonarch_workspace_bytes.argtypes = dims + [c_int, c_int, c_int]
+        L.vmonarch_set_workspace.argtypes = [c_void_p, c_size_t]
+        for name in ("vmonarch_attention", "vmonarch_attention_f32"):
+            getattr(L, name).argtypes = [c_void_p] * 4 + dims + [c_int, c_int, c_void_p]
+        for name in ("vmonarch_r_update", "vmonarch_r_update_f32"):
+            getattr(L, name).argtypes = [c_void_p] * 7 + dims + [c_float, c_float, c_void_p]
+        for name in ("vmonarch_l_update", "vmonarch_l_update_f32"):
+            getattr(L, name).argtypes = [c_void_p] * 7 + dims + [c_float, c_void_p]
+        for name in ("vmonarch_first_frame_attention", "vmonarch_first_frame_attention_f32"):
+            getattr(L, name).argtypes = [c_void_p] * 4 + dims + [c_void_p]
+        L.vmonarch_index_maps.argtypes = [c_int, c_int, c_int, c_void_p, c_void_p]
+        L.vmonarch_permute_tokens.argtypes = [c_void_p, c_void_p, c_int, c_int, c_int, c_int, c_int, c_int, c_int,
+                                              c_void_p]
+        _lib = L
+    return _lib
+
+
+def _check(rc: int) -> None:
+    if rc != 0:
+        raise VMonarchError(f"vmonarch error {rc}: {lib().vmonarch_last_error().decode()}")
+
+
+def _ptr(t):
+    if t is None:
+        return None
+    assert t.is_cuda and t.is_contiguous(), "device tensors must be contiguous CUDA tensors"
+    return c_void_p(t.data_ptr())
+
+
+def _stream():
+    return c_void_p(torch.cuda.current_stream().cuda_stream)
+
+
+def _suffix(t: torch.Tensor) -> str:
+    if t.dtype == torch.bfloat16:
+        return ""
+    if t.dtype == torch.float32:
+        return "_f32"
+    raise VMonarchError(f"unsupported dtype {t.dtype}")
+
+
+def version() -> int:
+    return lib().vmonarch_version()
+
+
+def set_cr_min(x: float) -> None:
+    _check(lib().vmonarch_set_cr_min(c_float(x)))
+
+
+def get_cr_min() -> float:
+    return float(lib().vmonarch_get_cr_min())
+
+
+def set_entropy_mode(mode: int) -> None:
+    _check(lib().vmonarch_set_entropy_mode(mode))
+
+
+def workspace_bytes(B, heads, T, Hs, Ws, d, iters, recompute, elem_bytes) -> int:
+    return int(lib().vmonarch_workspace_bytes(B, heads, T, Hs, Ws, d, iters, int(bool(recompute)), elem_bytes))
+
+
+def set_workspace(t) -> None:
+    """Hand a uint8 CUDA tensor to the library as scratch (None returns to the internal arena)."""
+    if t is None:
+        _check(lib().vmonarch_set_workspace(None, 0))
+    else:
+        _check(lib().vmonarch_set_workspace(_ptr(t), t.numel() * t.element_size()))
+
+
+def shutdown() -> None:
+    _check(lib().vmonarch_shutdown())
+
+
+def attention(q, k, v, T, Hs, Ws, iters=2, recompute=True, out=None):
+    """q, k, v: [B, heads, N, d] bf16 or f32 CUDA tensors -> out of the same shape."""
+    B, heads, N, d = q.shape
+    assert N == T * Hs * Ws and k.shape == q.shape and v.shape == q.shape
+    if out is None:
+        out = torch.empty_like(q)
+    fn = getattr(lib(), "vmonarch_attention" + _suffix(q))
+    _check(fn(_ptr(q), _ptr(k), _ptr(v), _ptr(out), B, heads, T, Hs, Ws, d, iters, int(bool(recompute)), _stream()))
+    return out
+
+
+def r_update(aR, cR, k, v, T, Hs, Ws, row_scale, cr_min):
+    """Returns (aL, cL, y or None); layouts [B, heads, T*b, d] and [B, heads, T*b]."""
+    B, heads, N, d = aR.shape
+    aL = torch.empty_like(aR)
+    cL = torch.empty((B, heads, N), dtype=torch.float32, device=aR.device)
+    y = torch.empty_like(aR) if v is not None else None
+    fn = getattr(lib(), "vmonarch_r_update" + _suffix(aR))
+    _check(fn(_ptr(aR), _ptr(cR), _ptr(k), _ptr(v), _ptr(aL), _ptr(cL), _ptr(y), B, heads, T, Hs, Ws, d,
+              c_float(row_scale), c_float(cr_min), _stream()))
+    return aL, cL, y
+
+
+def l_update(q, aL, cL, y, T, Hs, Ws, q_scale):
+    """Fitting sweep (y None): returns (aR, cR).  Last sweep (y given): returns out."""
+    B, heads, N, d = q.shape
+    fn = getattr(lib(), "vmonarch_l_update" + _suffix(q))
+    if y is None:
+        aR = torch.empty_like(q)
+        cR = torch.empty((B, heads, N), dtype=torch.float32, device=q.device)
+        _check(fn(_ptr(q), _ptr(aL), _ptr(cL), None, _ptr(aR), _ptr(cR), None, B, heads, T, Hs, Ws, d,
+                  c_float(q_scale), _stream()))
+        return aR, cR
+    out = torch.empty_like(q)
+    _check(fn(_ptr(q), _ptr(aL), _ptr(cL), _ptr(y), None, None, _ptr(out), B, heads, T, Hs, Ws, d,
+              c_float(q_scale), _stream()))
+    return out
+
+
+def first_frame_attention(q, k, v, T, Hs, Ws, out):
+    """Overwrites rows 0..b-1 of every head of `out` with exact attention over all keys."""
+    B, heads, N, d = q.shape
+    fn = getattr(lib(), "vmonarch_first_frame_attention" + _suffix(q))
+    _check(fn(_ptr(q), _ptr(k), _ptr(v), _ptr(out), B, heads, T, Hs, Ws, d, _stream()))
+    return out
+
+
+def index_maps(T, Hs, Ws):
+    """(perm, inv) as int32 CPU tensors."""
+    N = T * Hs * Ws
+    perm = torch.empty(N, dtype=torch.int32)
+    inv = torch.empty(N, dtype=torch.int32)
+    _check(lib().vmonarch_index_maps(T, Hs, Ws, c_void_p(perm.data_ptr()), c_void_p(inv.data_ptr())))
+    return perm, inv
+
+
+def permute_tokens(x, T, Hs, Ws, to_position_major=True):
+    B, heads, N, d = x.shape
+    out = torch.empty_like(x)
+    _check(lib().vmonarch_permute_tokens(_ptr(x), _ptr(out), B, heads, T, Hs, Ws, d * x.element_size(),
+                                         int(bool(to_position_major)), _stream()))
+    return out

@@ -1,0 +1,391 @@
+// C ABI of libvmonarch: argument validation, workspace management and the launch sequence of
+// the whole path (App. A monarch_attention loop + Sec. 3.3 recomputation).  See
+// include/vmonarch.h for the contract of every entry point.
+#include "../../include/vmonarch.h"
+
+#include <math.h>
+#include <stdarg.h>
+#include <stdio.h>
+#include <string.h>
+
+#include <mutex>
+
+#include "common.h"
+
+using namespace vm;
+
+namespace {
+
+thread_local char g_err[512] = "";
+float g_cr_min = 0.1f;
+int g_entropy_mode = VMONARCH_ENTROPY_ONLINE;
+
+std::mutex g_ws_mutex;
+void* g_user_ws = nullptr;
+size_t g_user_ws_bytes = 0;
+void* g_arena[64] = {nullptr};  // per device, library-owned
+size_t g_arena_bytes[64] = {0};
+
+int fail(int code, const char* fmt, ...) {
+  va_list ap;
+  va_start(ap, fmt);
+  vsnprintf(g_err, sizeof(g_err), fmt, ap);
+  va_end(ap);
+  return code;
+}
+
+int hip_fail(hipError_t e, const char* what) {
+  return fail(VMONARCH_ERR_HIP, "%s: %s", what, hipGetErrorString(e));
+}
+
+int make_dims(int B, int heads, int T, int Hs, int Ws, int d, Dims* dm) {
+  if (B <= 0 || heads <= 0 || T <= 0 || Hs <= 0 || Ws <= 0 || d <= 0)
+    return fail(VMONARCH_ERR_INVALID_ARG, "sizes must be positive (B=%d heads=%d T=%d Hs=%d Ws=%d d=%d)", B, heads, T,
+                Hs, Ws, d);
+  if (d > 256) return fail(VMONARCH_ERR_UNSUPPORTED, "d=%d exceeds 256", d);
+  long long bh = (long long)B * heads;
+  long long b = (long long)Hs * Ws;
+  long long N = b * T;
+  if (bh > 65535) return fail(VMONARCH_ERR_UNSUPPORTED, "B*heads=%lld exceeds 65535", bh);
+  if (T > 65535) return fail(VMONARCH_ERR_UNSUPPORTED, "T=%d exceeds 65535", T);
+  if (N > 0x7fffffffLL) return fail(VMONARCH_ERR_UNSUPPORTED, "N=%lld tokens per head exceeds 2^31-1", N);
+  dm->BH = (int)bh;
+  dm->T = T;
+  dm->b = (int)b;
+  dm->d = d;
+  dm->N = N;
+  return VMONARCH_OK;
+}
+
+size_t align_up(size_t x) { return (x + 255) & ~(size_t)255; }
+
+struct WsLayout {
+  size_t aL, aR, y, cL, cR, ff, total;
+};
+
+WsLayout ws_layout(const Dims& dm, int iters, int recompute, int elem_bytes) {
+  WsLayout w;
+  size_t tok = align_up((size_t)dm.BH * dm.N * dm.d * elem_bytes);
+  size_t sc = align_up((size_t)dm.BH * dm.N * sizeof(float));
+  size_t off = 0;
+  w.aL = off; off += tok;
+  w.y = off; off += tok;
+  w.cL = off; off += sc;
+  w.aR = off; if (iters > 1) off += tok;
+  w.cR = off; if (iters > 1) off += sc;
+  w.ff = off;
+  if (recompute && elem_bytes == 2 && flash_supported(dm)) off += align_up(first_frame_flash_scratch_bytes(dm));
+  w.total = off;
+  return w;
+}
+
+// Returns scratch of at least `bytes` on the current device, or nullptr with g_err set.
+void* get_workspace(size_t bytes, int* err) {
+  std::lock_guard<std::mutex> lk(g_ws_mutex);
+  *err = VMONARCH_OK;
+  if (g_user_ws != nullptr) {
+    if (g_user_ws_bytes < bytes) {
+      *err = fail(VMONARCH_ERR_WORKSPACE, "caller workspace has %zu bytes, %zu needed", g_user_ws_bytes, bytes);
+      return nullptr;
+    }
+    return g_user_ws;
+  }
+  int dev = 0;
+  hipError_t e = hipGetDevice(&dev);
+  if (e != hipSuccess || dev < 0 || dev >= 64) {
+    *err = fail(VMONARCH_ERR_HIP, "hipGetDevice failed");
+    return nullptr;
+  }
+  if (g_arena_bytes[dev] < bytes) {
+    if (g_arena[dev] != nullptr) {
+      (void)hipDeviceSynchronize();
+      (void)hipFree(g_arena[dev]);
+      g_arena[dev] = nullptr;
+      g_arena_bytes[dev] = 0;
+    }
+    e = hipMalloc(&g_arena[dev], bytes);
+    if (e != hipSuccess) {
+      g_arena[dev] = nullptr;
+      *err = fail(VMONARCH_ERR_WORKSPACE, "hipMalloc of %zu workspace bytes failed: %s", bytes, hipGetErrorString(e));
+      return nullptr;
+    }
+    g_arena_bytes[dev] = bytes;
+  }
+  return g_arena[dev];
+}
+
+template <typename E>
+int r_update_any(const E* aR, const float* cR, const E* k, const E* v, E* aL, float* cL, E* y, const Dims& dm,
+                 float row_scale, float cr_min, hipStream_t st);
+template <>
+int r_update_any<float>(const float* aR, const float* cR, const float* k, const float* v, float* aL, float* cL,
+                        float* y, const Dims& dm, float row_scale, float cr_min, hipStream_t st) {
+  hipError_t e = launch_r_update_generic<float>(aR, cR, k, v, aL, cL, y, dm, row_scale, cr_min, st);
+  return e == hipSuccess ? VMONARCH_OK : hip_fail(e, "r_update (plain-ALU f32) launch");
+}
+template <>
+int r_update_any<bf16_t>(const bf16_t* aR, const float* cR, const bf16_t* k, const bf16_t* v, bf16_t* aL, float* cL,
+                         bf16_t* y, const Dims& dm, float row_scale, float cr_min, hipStream_t st) {
+  hipError_t e;
+  if (flash_supported(dm))
+    e = launch_r_update_flash(aR, cR, k, v, aL, cL, y, dm, row_scale, cr_min, g_entropy_mode, st);
+  else
+    e = launch_r_update_generic<bf16_t>(aR, cR, k, v, aL, cL, y, dm, row_scale, cr_min, st);
+  return e == hipSuccess ? VMONARCH_OK : hip_fail(e, "r_update (bf16) launch");
+}
+
+template <typename E>
+int l_update_any(const E* q, const E* aL, const float* cL, const E* y, E* aR, float* cR, E* out, const Dims& dm,
+                 float q_scale, hipStream_t st);
+template <>
+int l_update_any<float>(const float* q, const float* aL, const float* cL, const float* y, float* aR, float* cR,
+                        float* out, const Dims& dm, float q_scale, hipStream_t st) {
+  if (dm.T > 200) return fail(VMONARCH_ERR_UNSUPPORTED, "plain-ALU L-update keeps a T x T block in LDS: T=%d > 200", dm.T);
+  hipError_t e = launch_l_update_generic<float>(q, aL, cL, y, aR, cR, out, dm, q_scale, st);
+  return e == hipSuccess ? VMONARCH_OK : hip_fail(e, "l_update (plain-ALU f32) launch");
+}
+template <>
+int l_update_any<bf16_t>(const bf16_t* q, const bf16_t* aL, const float* cL, const bf16_t* y, bf16_t* aR, float* cR,
+                         bf16_t* out, const Dims& dm, float q_scale, hipStream_t st) {
+  hipError_t e;
+  if (lpass_supported(dm)) {
+    e = launch_l_update_mfma(q, aL, cL, y, aR, cR, out, dm, q_scale, st);
+  } else {
+    if (dm.T > 200)
+      return fail(VMONARCH_ERR_UNSUPPORTED, "plain-ALU L-update keeps a T x T block in LDS: T=%d > 200", dm.T);
+    e = launch_l_update_generic<bf16_t>(q, aL, cL, y, aR, cR, out, dm, q_scale, st);
+  }
+  return e == hipSuccess ? VMONARCH_OK : hip_fail(e, "l_update (bf16) launch");
+}
+
+template <typename E>
+int first_frame_any(const E* q, const E* k, const E* v, E* out, void* scratch, size_t scratch_bytes, const Dims& dm,
+                    hipStream_t st);
+template <>
+int first_frame_any<float>(const float* q, const float* k, const float* v, float* out, void*, size_t, const Dims& dm,
+                           hipStream_t st) {
+  hipError_t e = launch_first_frame_generic<float>(q, k, v, out, dm, st);
+  return e == hipSuccess ? VMONARCH_OK : hip_fail(e, "first_frame (plain-ALU f32) launch");
+}
+template <>
+int first_frame_any<bf16_t>(const bf16_t* q, const bf16_t* k, const bf16_t* v, bf16_t* out, void* scratch,
+                            size_t scratch_bytes, const Dims& dm, hipStream_t st) {
+  hipError_t e;
+  if (flash_supported(dm))
+    e = launch_first_frame_flash(q, k, v, out, scratch, scratch_bytes, dm, st);
+  else
+    e = launch_first_frame_generic<bf16_t>(q, k, v, out, dm, st);
+  return e == hipSuccess ? VMONARCH_OK : hip_fail(e, "first_frame (bf16) launch");
+}
+
+template <typename E>
+int attention_impl(const void* q_, const void* k_, const void* v_, void* out_, int B, int heads, int T, int Hs, int Ws,
+                   int d, int iters, int recompute, void* stream) {
+  if (!q_ || !k_ || !v_ || !out_) return fail(VMONARCH_ERR_INVALID_ARG, "null tensor pointer");
+  if (iters < 1) return fail(VMONARCH_ERR_INVALID_ARG, "iters=%d must be >= 1", iters);
+  Dims dm;
+  int rc = make_dims(B, heads, T, Hs, Ws, d, &dm);
+  if (rc) return rc;
+  if (out_ == q_ || out_ == k_ || out_ == v_) return fail(VMONARCH_ERR_INVALID_ARG, "out aliases an input");
+  const E* q = (const E*)q_;
+  const E* k = (const E*)k_;
+  const E* v = (const E*)v_;
+  E* out = (E*)out_;
+  hipStream_t st = (hipStream_t)stream;
+  WsLayout w = ws_layout(dm, iters, recompute, (int)sizeof(E));
+  char* ws = (char*)get_workspace(w.total, &rc);  // w.total > 0: alpha_L, y and c_L are always needed
+  if (!ws) return rc;
+  E* aL = (E*)(ws + w.aL);
+  E* y = (E*)(ws + w.y);
+  float* cL = (float*)(ws + w.cL);
+  E* aR = (E*)(ws + w.aR);
+  float* cR = (float*)(ws + w.cR);
+  const float s = 1.0f / sqrtf((float)d);
+  const float cr_min = g_cr_min;
+  // App. A: aR = Q, cR = 1, then `iters` times (R-update; L-update); y = R V and O = L y
+  // ride on the last sweep.  Q carries 1/sqrt(d) through row_scale / q_scale.
+  for (int sweep = 0; sweep < iters; ++sweep) {
+    const bool last = sweep == iters - 1;
+    rc = r_update_any<E>(sweep == 0 ? q : aR, sweep == 0 ? nullptr : cR, k, last ? v : nullptr, aL, cL,
+                         last ? y : nullptr, dm, s, cr_min, st);
+    if (rc) return rc;
+    rc = l_update_any<E>(q, aL, cL, last ? y : nullptr, last ? nullptr : aR, last ? nullptr : cR, last ? out : nullptr,
+                         dm, s, st);
+    if (rc) return rc;
+  }
+  if (recompute) {
+    rc = first_frame_any<E>(q, k, v, out, ws + w.ff, w.total - w.ff, dm, st);
+    if (rc) return rc;
+  }
+  return VMONARCH_OK;
+}
+
+template <typename E>
+int r_update_impl(const void* aR, const float* cR, const void* k, const void* v, void* aL, float* cL, void* y, int B,
+                  int heads, int T, int Hs, int Ws, int d, float row_scale, float cr_min, void* stream) {
+  if (!aR || !k || !aL || !cL) return fail(VMONARCH_ERR_INVALID_ARG, "null tensor pointer");
+  if ((v == nullptr) != (y == nullptr)) return fail(VMONARCH_ERR_INVALID_ARG, "v and y_out must be given together");
+  if (!(row_scale > 0.f) || !(cr_min >= 0.f)) return fail(VMONARCH_ERR_INVALID_ARG, "row_scale must be > 0 and cr_min >= 0");
+  Dims dm;
+  int rc = make_dims(B, heads, T, Hs, Ws, d, &dm);
+  if (rc) return rc;
+  return r_update_any<E>((const E*)aR, cR, (const E*)k, (const E*)v, (E*)aL, cL, (E*)y, dm, row_scale, cr_min,
+                         (hipStream_t)stream);
+}
+
+template <typename E>
+int l_update_impl(const void* q, const void* aL, const float* cL, const void* y, void* aR, float* cR, void* out, int B,
+                  int heads, int T, int Hs, int Ws, int d, float q_scale, void* stream) {
+  if (!q || !aL || !cL) return fail(VMONARCH_ERR_INVALID_ARG, "null tensor pointer");
+  const bool fin = y != nullptr;
+  if (fin && (!out || aR || cR)) return fail(VMONARCH_ERR_INVALID_ARG, "with y, give out and neither aR_out nor cR_out");
+  if (!fin && (!aR || !cR || out)) return fail(VMONARCH_ERR_INVALID_ARG, "without y, give aR_out and cR_out and not out");
+  Dims dm;
+  int rc = make_dims(B, heads, T, Hs, Ws, d, &dm);
+  if (rc) return rc;
+  return l_update_any<E>((const E*)q, (const E*)aL, cL, (const E*)y, (E*)aR, cR, (E*)out, dm, q_scale,
+                         (hipStream_t)stream);
+}
+
+template <typename E>
+int first_frame_impl(const void* q, const void* k, const void* v, void* out, int B, int heads, int T, int Hs, int Ws,
+                     int d, void* stream) {
+  if (!q || !k || !v || !out) return fail(VMONARCH_ERR_INVALID_ARG, "null tensor pointer");
+  Dims dm;
+  int rc = make_dims(B, heads, T, Hs, Ws, d, &dm);
+  if (rc) return rc;
+  void* scratch = nullptr;
+  size_t sb = 0;
+  if (sizeof(E) == 2 && flash_supported(dm)) {
+    sb = align_up(first_frame_flash_scratch_bytes(dm));
+    if (sb > 0) {
+      scratch = get_workspace(sb, &rc);
+      if (!scratch) return rc;
+    }
+  }
+  return first_frame_any<E>((const E*)q, (const E*)k, (const E*)v, (E*)out, scratch, sb, dm, (hipStream_t)stream);
+}
+
+}  // namespace
+
+extern "C" {
+#pragma GCC visibility push(default)
+
+int vmonarch_version(void) { return 100; }
+const char* vmonarch_last_error(void) { return g_err; }
+
+int vmonarch_set_cr_min(float cr_min) {
+  if (!(cr_min >= 0.f)) return fail(VMONARCH_ERR_INVALID_ARG, "cr_min must be >= 0");
+  g_cr_min = cr_min;
+  return VMONARCH_OK;
+}
+float vmonarch_get_cr_min(void) { return g_cr_min; }
+
+int vmonarch_set_entropy_mode(int mode) {
+  if (mode != VMONARCH_ENTROPY_ONLINE && mode != VMONARCH_ENTROPY_IDENTITY)
+    return fail(VMONARCH_ERR_INVALID_ARG, "unknown entropy mode %d", mode);
+  g_entropy_mode = mode;
+  return VMONARCH_OK;
+}
+int vmonarch_get_entropy_mode(void) { return g_entropy_mode; }
+
+size_t vmonarch_workspace_bytes(int B, int heads, int T, int Hs, int Ws, int d, int iters, int recompute,
+                                int elem_bytes) {
+  Dims dm;
+  if (iters < 1 || (elem_bytes != 2 && elem_bytes != 4)) return 0;
+  if (make_dims(B, heads, T, Hs, Ws, d, &dm)) return 0;
+  return ws_layout(dm, iters, recompute, elem_bytes).total;
+}
+
+int vmonarch_set_workspace(void* dev_ptr, size_t bytes) {
+  std::lock_guard<std::mutex> lk(g_ws_mutex);
+  if ((dev_ptr == nullptr) != (bytes == 0)) return fail(VMONARCH_ERR_INVALID_ARG, "pointer and size must both be zero or both non-zero");
+  if (((uintptr_t)dev_ptr & 255) != 0) return fail(VMONARCH_ERR_INVALID_ARG, "workspace must be 256-byte aligned");
+  g_user_ws = dev_ptr;
+  g_user_ws_bytes = bytes;
+  return VMONARCH_OK;
+}
+
+int vmonarch_shutdown(void) {
+  std::lock_guard<std::mutex> lk(g_ws_mutex);
+  int cur = 0;
+  (void)hipGetDevice(&cur);
+  for (int dev = 0; dev < 64; ++dev) {
+    if (g_arena[dev] != nullptr) {
+      (void)hipSetDevice(dev);
+      (void)hipDeviceSynchronize();
+      (void)hipFree(g_arena[dev]);
+      g_arena[dev] = nullptr;
+      g_arena_bytes[dev] = 0;
+    }
+  }
+  (void)hipSetDevice(cur);
+  g_user_ws = nullptr;
+  g_user_ws_bytes = 0;
+  return VMONARCH_OK;
+}
+
+int vmonarch_attention(const void* q, const void* k, const void* v, void* out, int B, int heads, int T, int Hs, int Ws,
+                       int d, int iters, int recompute, void* stream) {
+  return attention_impl<bf16_t>(q, k, v, out, B, heads, T, Hs, Ws, d, iters, recompute, stream);
+}
+int vmonarch_attention_f32(const void* q, const void* k, const void* v, void* out, int B, int heads, int T, int Hs,
+                           int Ws, int d, int iters, int recompute, void* stream) {
+  return attention_impl<float>(q, k, v, out, B, heads, T, Hs, Ws, d, iters, recompute, stream);
+}
+
+int vmonarch_r_update(const void* aR, const float* cR, const void* k, const void* v, void* aL_out, float* cL_out,
+                      void* y_out, int B, int heads, int T, int Hs, int Ws, int d, float row_scale, float cr_min,
+                      void* stream) {
+  return r_update_impl<bf16_t>(aR, cR, k, v, aL_out, cL_out, y_out, B, heads, T, Hs, Ws, d, row_scale, cr_min, stream);
+}
+int vmonarch_r_update_f32(const void* aR, const float* cR, const void* k, const void* v, void* aL_out, float* cL_out,
+                          void* y_out, int B, int heads, int T, int Hs, int Ws, int d, float row_scale, float cr_min,
+                          void* stream) {
+  return r_update_impl<float>(aR, cR, k, v, aL_out, cL_out, y_out, B, heads, T, Hs, Ws, d, row_scale, cr_min, stream);
+}
+
+int vmonarch_l_update(const void* q, const void* aL, const float* cL, const void* y, void* aR_out, float* cR_out,
+                      void* out, int B, int heads, int T, int Hs, int Ws, int d, float q_scale, void* stream) {
+  return l_update_impl<bf16_t>(q, aL, cL, y, aR_out, cR_out, out, B, heads, T, Hs, Ws, d, q_scale, stream);
+}
+int vmonarch_l_update_f32(const void* q, const void* aL, const float* cL, const void* y, void* aR_out, float* cR_out,
+                          void* out, int B, int heads, int T, int Hs, int Ws, int d, float q_scale, void* stream) {
+  return l_update_impl<float>(q, aL, cL, y, aR_out, cR_out, out, B, heads, T, Hs, Ws, d, q_scale, stream);
+}
+
+int vmonarch_first_frame_attention(const void* q, const void* k, const void* v, void* out, int B, int heads, int T,
+                                   int Hs, int Ws, int d, void* stream) {
+  return first_frame_impl<bf16_t>(q, k, v, out, B, heads, T, Hs, Ws, d, stream);
+}
+int vmonarch_first_frame_attention_f32(const void* q, const void* k, const void* v, void* out, int B, int heads, int T,
+                                       int Hs, int Ws, int d, void* stream) {
+  return first_frame_impl<float>(q, k, v, out, B, heads, T, Hs, Ws, d, stream);
+}
+
+int vmonarch_index_maps(int T, int Hs, int Ws, int32_t* perm_host, int32_t* inv_host) {
+  if (!perm_host || !inv_host) return fail(VMONARCH_ERR_INVALID_ARG, "null table pointer");
+  if (T <= 0 || Hs <= 0 || Ws <= 0) return fail(VMONARCH_ERR_INVALID_ARG, "sizes must be positive");
+  long long b = (long long)Hs * Ws, N = b * T;
+  if (N > 0x7fffffffLL) return fail(VMONARCH_ERR_UNSUPPORTED, "N=%lld does not fit int32", N);
+  for (long long i = 0; i < b; ++i)
+    for (long long j = 0; j < T; ++j) {
+      perm_host[i * T + j] = (int32_t)(j * b + i);
+      inv_host[j * b + i] = (int32_t)(i * T + j);
+    }
+  return VMONARCH_OK;
+}
+
+int vmonarch_permute_tokens(const void* in, void* out, int B, int heads, int T, int Hs, int Ws, int row_bytes,
+                            int to_position_major, void* stream) {
+  if (!in || !out || in == out) return fail(VMONARCH_ERR_INVALID_ARG, "null or aliased tensor pointer");
+  if (row_bytes <= 0 || (row_bytes & 3)) return fail(VMONARCH_ERR_INVALID_ARG, "row_bytes must be a positive multiple of 4");
+  Dims dm;
+  int rc = make_dims(B, heads, T, Hs, Ws, 1, &dm);
+  if (rc) return rc;
+  hipError_t e = launch_permute_tokens(in, out, dm, row_bytes, to_position_major, (hipStream_t)stream);
+  return e == hipSuccess ? VMONARCH_OK : hip_fail(e, "permute_tokens launch");
+}
+
+#pragma GCC visibility pop
+}  // extern "C"

@@ -1,0 +1,67 @@
+// Internal declarations shared by the translation units of libvmonarch (not part of the ABI).
+#pragma once
+#include <hip/hip_runtime.h>
+#include <stddef.h>
+#include <stdint.h>
+
+namespace vm {
+
+typedef uint16_t bf16_t;  // raw bfloat16 bits in memory
+
+typedef __attribute__((__vector_size__(8 * sizeof(__bf16)))) __bf16 bf16x8;
+typedef __attribute__((__vector_size__(4 * sizeof(__bf16)))) __bf16 bf16x4;
+typedef __attribute__((__vector_size__(16 * sizeof(float)))) float f32x16;
+typedef __attribute__((__vector_size__(4 * sizeof(float)))) float f32x4;
+
+__device__ __forceinline__ float bf16_to_f32(bf16_t h) { return __uint_as_float(((uint32_t)h) << 16); }
+// round-to-nearest-even; NaN stays NaN
+__device__ __forceinline__ bf16_t f32_to_bf16(float f) {
+  uint32_t u = __float_as_uint(f);
+  if ((u & 0x7fffffffu) > 0x7f800000u) return (bf16_t)((u >> 16) | 0x40u);
+  u += 0x7fffu + ((u >> 16) & 1u);
+  return (bf16_t)(u >> 16);
+}
+template <typename E> __device__ __forceinline__ float load_f(const E* p);
+template <> __device__ __forceinline__ float load_f<float>(const float* p) { return *p; }
+template <> __device__ __forceinline__ float load_f<bf16_t>(const bf16_t* p) { return bf16_to_f32(*p); }
+template <typename E> __device__ __forceinline__ void store_f(E* p, float x);
+template <> __device__ __forceinline__ void store_f<float>(float* p, float x) { *p = x; }
+template <> __device__ __forceinline__ void store_f<bf16_t>(bf16_t* p, float x) { *p = f32_to_bf16(x); }
+
+// Problem description handed to every launcher.
+struct Dims {
+  int BH;     // B * heads
+  int T;      // frames (m)
+  int b;      // spatial positions per frame
+  int d;      // head dimension
+  long long N;  // T * b
+};
+
+// ---- launchers (host) -------------------------------------------------------------
+// generic.hip : plain-ALU kernels, any T, b, d <= 256, element type float or bf16
+template <typename E>
+hipError_t launch_r_update_generic(const E* aR, const float* cR, const E* k, const E* v, E* aL, float* cL,
+                                   E* y, const Dims& dm, float row_scale, float cr_min, hipStream_t st);
+template <typename E>
+hipError_t launch_l_update_generic(const E* q, const E* aL, const float* cL, const E* y, E* aR, float* cR,
+                                   E* out, const Dims& dm, float q_scale, hipStream_t st);
+template <typename E>
+hipError_t launch_first_frame_generic(const E* q, const E* k, const E* v, E* out, const Dims& dm, hipStream_t st);
+hipError_t launch_permute_tokens(const void* in, void* out, const Dims& dm, int row_bytes, int to_pos_major,
+                                 hipStream_t st);
+
+// flash.hip : bf16 MFMA blocked-softmax kernels (d == 128)
+bool flash_supported(const Dims& dm);
+hipError_t launch_r_update_flash(const bf16_t* aR, const float* cR, const bf16_t* k, const bf16_t* v, bf16_t* aL,
+                                 float* cL, bf16_t* y, const Dims& dm, float row_scale, float cr_min,
+                                 int entropy_mode, hipStream_t st);
+size_t first_frame_flash_scratch_bytes(const Dims& dm);
+hipError_t launch_first_frame_flash(const bf16_t* q, const bf16_t* k, const bf16_t* v, bf16_t* out, void* scratch,
+                                    size_t scratch_bytes, const Dims& dm, hipStream_t st);
+
+// lpass.hip : bf16 MFMA temporal kernels (d == 128, T <= 128)
+bool lpass_supported(const Dims& dm);
+hipError_t launch_l_update_mfma(const bf16_t* q, const bf16_t* aL, const float* cL, const bf16_t* y, bf16_t* aR,
+                                float* cR, bf16_t* out, const Dims& dm, float q_scale, hipStream_t st);
+
+}  // namespace vm

@@ -1,0 +1,592 @@
+// bf16 MFMA kernels for the blocked-softmax passes of spatio-temporal Monarch attention on
+// gfx950: the R-update (Eq. R + Eq. alpha_L/c_L, computed as Alg. 1 with the running
+// max / sum / entropy of App. B) and the first-frame recomputation (Sec. 3.3).
+//
+// One workgroup = 4 waves = 256 query rows; each wave owns 64 query rows (two 32-wide
+// tiles) for the whole key loop.  Keys (and values) stream through LDS in 64-row tiles,
+// double buffered.  Both contractions use v_mfma_f32_32x32x16_bf16:
+//
+//   S^T = K Q^T     A = K rows read from LDS (ds_read_b128), B = Q^T held in registers.
+//                   In the result lane (q, g) holds the logits of query q for 16 of the 32
+//                   keys, so the row statistics (max, sum, entropy) are per-lane scalars
+//                   and need one exchange with lane^32 for the max only.
+//   O^T += X^T P^T  A = X^T (X = K for alpha_L, X = V for y) fetched from the same
+//                   row-major LDS tile with the LDS transpose read (ds_read_b64_tr_b16),
+//                   B = P^T, which is the S^T accumulator converted to bf16 in place:
+//                   eight consecutive accumulator registers are exactly one B operand.
+//
+// LDS rows are 256 B (d = 128); the 16-byte chunk c of key row r is stored at chunk
+// c ^ swz(r) so that both the row-wise b128 reads and the transpose reads spread over
+// all banks.
+#include "../../include/vmonarch.h"
+#include <type_traits>
+
+#include "common.h"
+
+namespace vm {
+
+namespace {
+
+constexpr int D = 128;          // head dimension handled here
+constexpr int BQ = 256;         // query rows per workgroup
+constexpr int BK = 64;          // key rows per LDS tile
+constexpr int ROW_BYTES = D * 2;
+constexpr int TILE_BYTES = BK * ROW_BYTES;  // 16 KB
+constexpr float LOG2E = 1.4426950408889634f;
+constexpr float LN2 = 0.6931471805599453f;
+constexpr float RESCALE_TH = 8.0f;  // rescale the accumulators only when a row max grows by 2^8
+constexpr float NEG_BIG = -1.0e30f;
+
+struct FlashParams {
+  const bf16_t* q;      // query rows
+  const float* cR;      // per query row, may be null (= 1)
+  const bf16_t* k;
+  const bf16_t* v;
+  bf16_t* outk;         // softmax(z) K   (alpha_L)
+  bf16_t* outv;         // softmax(z) V   (y, or the first-frame output)
+  float* cl;            // sum p log p    (c_L)
+  float* part_o;        // split mode: [split][problem][nq][D] normalised partial outputs
+  float* part_lse;      // split mode: [split][problem][nq] log2-sum-exp of the partial
+  long long q_rows_per_problem;  // row distance between problems in q / cR / outputs
+  long long k_rows_per_problem;  // row distance between problems in k / v
+  int nq;               // query rows per problem
+  int nk;               // key rows per problem
+  int nqb;              // query blocks per problem
+  int nsplit;           // key splits per (problem, query block)
+  int keys_per_split;   // multiple of BK
+  int total_blocks;     // nproblems * nqb * nsplit
+  int blocks_per_xcd;   // ceil(total_blocks / 8)
+  float row_scale;
+  float cr_min;
+};
+
+__device__ __forceinline__ int swz(int key) {
+  int x = key & 15;
+  return ((x & 3) << 2) | (x >> 2);
+}
+
+__device__ __forceinline__ bf16x8 lds_read_b128(const char* p) { return *reinterpret_cast<const bf16x8*>(p); }
+
+__device__ __forceinline__ bf16x4 lds_read_tr(const char* p) {
+  return __builtin_amdgcn_ds_read_tr16_b64_v4bf16(
+      (bf16x4 __attribute__((address_space(3)))*)(reinterpret_cast<const bf16x4*>(p)));
+}
+
+__device__ __forceinline__ uint32_t pack_bf16(float a, float b) {
+  // two round-to-nearest-even conversions; the compiler emits v_cvt_pk_bf16_f32
+  typedef __attribute__((__vector_size__(2 * sizeof(__bf16)))) __bf16 bf16x2;
+  bf16x2 r;
+  r[0] = (__bf16)a;
+  r[1] = (__bf16)b;
+  uint32_t u;
+  __builtin_memcpy(&u, &r, 4);
+  return u;
+}
+
+// acc *= alpha for an MFMA accumulator tile that lives in accumulation registers.  VALU
+// instructions cannot address those, so each element takes the read / multiply / write
+// round trip explicitly; spelled as inline assembly so that the register allocator keeps the
+// tile in accumulation registers instead of migrating it to the (scarcer) vector registers.
+// The caller brackets a batch of these with s_nop padding for the MFMA <-> VALU hazards.
+__device__ __forceinline__ void scale_acc(f32x16& acc, float alpha) {
+#pragma unroll
+  for (int r = 0; r < 16; ++r) {
+    float in = acc[r], out, tmp;
+    asm volatile("v_accvgpr_read_b32 %0, %2\n\tv_mul_f32 %0, %0, %3\n\tv_accvgpr_write_b32 %1, %0"
+                 : "=&v"(tmp), "=a"(out)
+                 : "a"(in), "v"(alpha));
+    acc[r] = out;
+  }
+}
+
+// Row maximum of one 32-key sub-tile for one 32-query tile.  `s` holds the raw logits
+// (aR . K) of query `lane & 31` for keys {8c + 4g + r}; the partner lane (lane ^ 32) holds the
+// other 16 keys.  Keys at or beyond `keys_left` are ignored when TAIL.
+template <bool TAIL>
+__device__ __forceinline__ float subtile_max(const f32x16& s, int g, int keys_left) {
+  float sv[16];
+#pragma unroll
+  for (int r = 0; r < 16; ++r) {
+    sv[r] = s[r];
+    if (TAIL) {
+      int key = 8 * (r >> 2) + 4 * g + (r & 3);
+      if (key >= keys_left) sv[r] = -3.0e38f;
+    }
+  }
+  float mx = fmaxf(fmaxf(sv[0], sv[1]), sv[2]);
+#pragma unroll
+  for (int r = 3; r < 15; r += 2) mx = fmaxf(fmaxf(mx, sv[r]), sv[r + 1]);
+  mx = fmaxf(mx, sv[15]);
+  return fmaxf(mx, __shfl_xor(mx, 32));
+}
+
+// Probabilities of the sub-tile relative to the reference max `msc` (log2 units):
+// t = s * sc - msc, p = 2^t.  `pb[0..1]` receive the two bf16 B operands (16 keys each) of
+// the O^T += X^T P^T products.  Running sums:
+//   lt = sum of the bf16-ROUNDED p (v_dot2 against ones): the accumulators are divided by
+//        this one, so that the output is an exact convex combination of the rows with
+//        slightly perturbed weights; dividing by the unrounded sum instead leaves a 2^-9
+//        relative error on rows dominated by one key;
+//   l  = sum p and h = sum p * t in full precision (ENT != 0 / ENT == 1): Alg. 1's
+//        statistics for log-sum-exp and entropy.
+template <int ENT, bool TAIL>
+__device__ __forceinline__ void subtile_probs(const f32x16& s, float sc, float msc, float& lt, float& l, float& h,
+                                              bf16x8 pb[2], int g, int keys_left) {
+  typedef __attribute__((__vector_size__(2 * sizeof(__bf16)))) __bf16 bf16x2;
+  bf16x2 ones2;
+  ones2[0] = (__bf16)1.0f;
+  ones2[1] = (__bf16)1.0f;
+  float p[16];
+#pragma unroll
+  for (int r = 0; r < 16; ++r) {
+    float t = __builtin_fmaf(s[r], sc, -msc);
+    if (TAIL) {
+      int key = 8 * (r >> 2) + 4 * g + (r & 3);
+      if (key >= keys_left) t = -1000.0f;
+    }
+    p[r] = __builtin_amdgcn_exp2f(t);
+    if (ENT != 0) l += p[r];
+    if (ENT == 1) h = __builtin_fmaf(p[r], t, h);
+  }
+#pragma unroll
+  for (int c = 0; c < 2; ++c) {
+    uint32_t w[4];
+#pragma unroll
+    for (int e = 0; e < 4; ++e) {
+      w[e] = pack_bf16(p[8 * c + 2 * e], p[8 * c + 2 * e + 1]);
+      bf16x2 pr;
+      __builtin_memcpy(&pr, &w[e], 4);
+      lt = __builtin_amdgcn_fdot2_f32_bf16(pr, ones2, lt, false);
+    }
+    __builtin_memcpy(&pb[c], w, 16);
+  }
+}
+
+template <bool OUT_K, bool OUT_V, int ENT, bool SPLIT>
+__global__ void __launch_bounds__(256) __attribute__((amdgpu_waves_per_eu(1, 1))) flash_kernel(FlashParams P) {
+  extern __shared__ __attribute__((aligned(16))) char smem[];  // [3 buffers][K|V][64 rows][256 B]
+
+  // XCD-aware placement: hardware deals workgroups to the 8 XCDs round-robin, so give each
+  // XCD one contiguous range of work items; the query blocks of one (head, frame) then share
+  // that XCD's L2 copy of the frame's K and V.
+  const int bid = blockIdx.x;
+  const int wid = (bid & 7) * P.blocks_per_xcd + (bid >> 3);
+  if (wid >= P.total_blocks) return;
+  const int per_problem = P.nqb * P.nsplit;
+  const int prob = wid / per_problem;
+  const int rem = wid - prob * per_problem;
+  const int qb = rem / P.nsplit;
+  const int split = rem - qb * P.nsplit;
+
+  const int tid = threadIdx.x;
+  const int wave = tid >> 6;
+  const int lane = tid & 63;
+  const int ql = lane & 31;
+  const int g = lane >> 5;
+
+  const int kbeg = split * P.keys_per_split;
+  const int kend = min(P.nk, kbeg + P.keys_per_split);
+  const int nkeys = kend - kbeg;
+  const int ntiles = (nkeys + BK - 1) / BK;
+
+  const long long qrow0 = (long long)prob * P.q_rows_per_problem;
+  const bf16_t* kbase = P.k + ((long long)prob * P.k_rows_per_problem + kbeg) * D;
+  const bf16_t* vbase = OUT_V ? P.v + ((long long)prob * P.k_rows_per_problem + kbeg) * D : nullptr;
+
+  // ---- queries: B operand of S^T = K Q^T, kept in registers -------------------------
+  bf16x8 qreg[2][8];
+  float sc[2];
+  int qrow[2];
+  bool qvalid[2];
+#pragma unroll
+  for (int qt = 0; qt < 2; ++qt) {
+    int r = qb * BQ + wave * 64 + qt * 32 + ql;
+    qvalid[qt] = r < P.nq;
+    qrow[qt] = qvalid[qt] ? r : P.nq - 1;
+    const bf16_t* qp = P.q + (qrow0 + qrow[qt]) * D + 8 * g;
+#pragma unroll
+    for (int ks = 0; ks < 8; ++ks) qreg[qt][ks] = *reinterpret_cast<const bf16x8*>(qp + 16 * ks);
+    float c = P.cR ? P.cR[qrow0 + qrow[qt]] : 1.0f;
+    c = fmaxf(c, P.cr_min);
+    sc[qt] = P.row_scale * LOG2E / c;
+  }
+
+  // ---- LDS addressing ----------------------------------------------------------------
+  // staging: global -> LDS directly (global_load_lds_dwordx4).  One wave instruction fills 64
+  // consecutive 16-byte slots (4 key rows); slot = key * 16 + physical chunk.  Wave w issues
+  // the instructions for key rows 16 r + 4 w .. + 3 (r = 0..3); each lane fetches the logical
+  // chunk that belongs in its slot.  Rows past the end of the key range are clamped to the
+  // last valid row (finite data that the tail mask removes again).
+  const int st_key = 4 * wave + (lane >> 4);             // + 16 r
+  const int st_lc = (lane & 15) ^ swz(st_key);
+  // row reads (A of S^T): key row = 32 st + ql, logical chunk 2 ks + g
+  int a_off[8];
+#pragma unroll
+  for (int ks = 0; ks < 8; ++ks) a_off[ks] = ql * ROW_BYTES + (((2 * ks + g) ^ swz(ql)) << 4);
+  // transpose reads (A of O^T += X^T P^T): 16-lane group u = lane / 16 -> g = u / 2, channel
+  // half u & 1; lane r' of the group supplies key (r' / 4) and channels 4 (r' & 3) .. + 3
+  int t_off[4][2];
+  {
+    const int rp = lane & 15;
+    const int chh = (lane >> 4) & 1;
+#pragma unroll
+    for (int ct = 0; ct < 4; ++ct)
+#pragma unroll
+      for (int hh = 0; hh < 2; ++hh) {
+        int key = 8 * hh + 4 * g + (rp >> 2);  // + 32 st + 16 c' added as an immediate
+        int lc = 4 * ct + 2 * chh + ((rp >> 1) & 1);
+        t_off[ct][hh] = key * ROW_BYTES + ((lc ^ swz(key)) << 4) + ((rp & 1) << 3);
+      }
+  }
+
+  // ---- accumulators --------------------------------------------------------------------
+  f32x16 ok[2][4], ov[2][4];
+#pragma unroll
+  for (int qt = 0; qt < 2; ++qt)
+#pragma unroll
+    for (int ct = 0; ct < 4; ++ct)
+#pragma unroll
+      for (int r = 0; r < 16; ++r) {
+        if (OUT_K) ok[qt][ct][r] = 0.f;
+        if (OUT_V) ov[qt][ct][r] = 0.f;
+      }
+  float msc[2] = {NEG_BIG, NEG_BIG}, ltil[2] = {0.f, 0.f}, lsum[2] = {0.f, 0.f}, hsum[2] = {0.f, 0.f};
+
+  // ---- tile staging ----------------------------------------------------------------------
+  auto issue_tile = [&](int t, int buf) {
+    char* kb = smem + buf * 2 * TILE_BYTES;
+#pragma unroll
+    for (int r = 0; r < 4; ++r) {
+      int key = min(t * BK + 16 * r + st_key, nkeys - 1);
+      const bf16_t* src = kbase + (long long)key * D + st_lc * 8;
+      char* dst = kb + (16 * r + 4 * wave) * ROW_BYTES;  // wave-uniform; lane lands at + 16 * lane
+      __builtin_amdgcn_global_load_lds((const void __attribute__((address_space(1)))*)src,
+                                       (void __attribute__((address_space(3)))*)dst, 16, 0, 0);
+      if (OUT_V) {
+        const bf16_t* vsrc = vbase + (long long)key * D + st_lc * 8;
+        __builtin_amdgcn_global_load_lds((const void __attribute__((address_space(1)))*)vsrc,
+                                         (void __attribute__((address_space(3)))*)(dst + TILE_BYTES), 16, 0, 0);
+      }
+    }
+  };
+
+  // One pipeline step = one 32-key sub-tile n of the key range:
+  //   (a) start S^T of sub-tile n+1 (MFMA) and, meanwhile, find the row maxima of sub-tile n;
+  //   (b) if some row maximum outgrew its reference by more than 2^RESCALE_TH, move the
+  //       references and rescale that query tile's statistics and accumulators (rare);
+  //   (c) p = 2^t, running sums, bf16 P^T;  (d) O^T += X^T P^T.
+  // Steps alternate between two logit buffers, so nothing is copied.
+  auto logits = [&](const char* ktile, int st, f32x16 (&sacc)[2]) {
+#pragma unroll
+    for (int qt = 0; qt < 2; ++qt)
+#pragma unroll
+      for (int r = 0; r < 16; ++r) sacc[qt][r] = 0.f;
+#pragma unroll
+    for (int ks = 0; ks < 8; ++ks) {
+      bf16x8 a = lds_read_b128(ktile + st * 32 * ROW_BYTES + a_off[ks]);
+#pragma unroll
+      for (int qt = 0; qt < 2; ++qt)
+        sacc[qt] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(a, qreg[qt][ks], sacc[qt], 0, 0, 0);
+    }
+  };
+  static_assert(!(OUT_K && OUT_V), "one accumulator set per pass (see launch_r_update_flash)");
+  constexpr bool S_AHEAD = true;
+  auto step = [&](auto tail_c, auto next_c, f32x16 (&scur)[2], f32x16 (&snext)[2], const char* ktile, int st,
+                  const char* next_ktile, int next_st, int keys_left) {
+    constexpr bool TAIL = decltype(tail_c)::value;
+    constexpr bool HAS_NEXT = decltype(next_c)::value;
+    if (S_AHEAD) {
+      if (HAS_NEXT) logits(next_ktile, next_st, snext);
+    } else {
+      logits(ktile, st, scur);
+    }
+    float cand[2];
+    bool grow = false;
+#pragma unroll
+    for (int qt = 0; qt < 2; ++qt) {
+      cand[qt] = subtile_max<TAIL>(scur[qt], g, keys_left) * sc[qt];
+      grow = grow || (cand[qt] > msc[qt] + RESCALE_TH);
+    }
+    if (__any(grow)) {
+      asm volatile("s_nop 15\n\ts_nop 15" ::: "memory");  // let in-flight MFMA results retire
+#pragma unroll
+      for (int qt = 0; qt < 2; ++qt) {
+        float mnew = fmaxf(msc[qt], cand[qt]);
+        float dl = msc[qt] - mnew;  // log2 of the rescale factor, <= 0
+        float alpha = __builtin_amdgcn_exp2f(dl);
+        if (ENT == 1) hsum[qt] = alpha * (hsum[qt] + dl * lsum[qt]);  // h <- a h + a log(a) l
+        if (ENT != 0) lsum[qt] *= alpha;
+        ltil[qt] *= alpha;
+        msc[qt] = mnew;
+#pragma unroll
+        for (int ct = 0; ct < 4; ++ct) {
+          if (OUT_K) scale_acc(ok[qt][ct], alpha);
+          if (OUT_V) scale_acc(ov[qt][ct], alpha);
+        }
+      }
+      asm volatile("s_nop 7\n\ts_nop 7" ::: "memory");  // accumulator writes settle before the next MFMA
+    }
+    bf16x8 pb[2][2];
+#pragma unroll
+    for (int qt = 0; qt < 2; ++qt)
+      subtile_probs<ENT, TAIL>(scur[qt], sc[qt], msc[qt], ltil[qt], lsum[qt], hsum[qt], pb[qt], g, keys_left);
+    const char* vtile = ktile + TILE_BYTES;
+#pragma unroll
+    for (int c = 0; c < 2; ++c) {
+      const int koff = (st * 32 + c * 16) * ROW_BYTES;
+#pragma unroll
+      for (int ct = 0; ct < 4; ++ct) {
+        if (OUT_K) {
+          bf16x4 lo = lds_read_tr(ktile + koff + t_off[ct][0]);
+          bf16x4 hi = lds_read_tr(ktile + koff + t_off[ct][1]);
+          bf16x8 a = __builtin_shufflevector(lo, hi, 0, 1, 2, 3, 4, 5, 6, 7);
+#pragma unroll
+          for (int qt = 0; qt < 2; ++qt)
+            ok[qt][ct] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(a, pb[qt][c], ok[qt][ct], 0, 0, 0);
+        }
+        if (OUT_V) {
+          bf16x4 lo = lds_read_tr(vtile + koff + t_off[ct][0]);
+          bf16x4 hi = lds_read_tr(vtile + koff + t_off[ct][1]);
+          bf16x8 a = __builtin_shufflevector(lo, hi, 0, 1, 2, 3, 4, 5, 6, 7);
+#pragma unroll
+          for (int qt = 0; qt < 2; ++qt)
+            ov[qt][ct] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(a, pb[qt][c], ov[qt][ct], 0, 0, 0);
+        }
+      }
+    }
+  };
+  using std::false_type;
+  using std::true_type;
+
+  if (ntiles > 0) {
+    // Three LDS buffers: while tile t is consumed, tile t+1 is resident (its first sub-tile
+    // is needed one step ahead) and tile t+2 is in flight.
+    issue_tile(0, 0);
+    if (ntiles > 1) issue_tile(1, 1);
+    asm volatile("s_waitcnt vmcnt(0)" ::: "memory");
+    __syncthreads();
+    f32x16 sA[2], sB[2];
+    if (S_AHEAD) logits(smem, 0, sA);
+    int buf = 0;  // buffer of tile t
+    for (int t = 0; t < ntiles - 1; ++t) {
+      if (t > 0) {
+        asm volatile("s_waitcnt vmcnt(0)" ::: "memory");
+        __syncthreads();  // tile t+1 has landed for everyone; everyone is done with tile t-1
+      }
+      const int nbuf = buf == 2 ? 0 : buf + 1;
+      if (t + 2 < ntiles) issue_tile(t + 2, nbuf == 2 ? 0 : nbuf + 1);
+      const char* kt = smem + buf * 2 * TILE_BYTES;
+      const char* kn = smem + nbuf * 2 * TILE_BYTES;
+      step(false_type{}, true_type{}, sA, sB, kt, 0, kt, 1, 32);
+      step(false_type{}, true_type{}, sB, sA, kt, 1, kn, 0, 32);
+      buf = nbuf;
+    }
+    {
+      if (ntiles > 1) {
+        asm volatile("s_waitcnt vmcnt(0)" ::: "memory");
+        __syncthreads();
+      }
+      const char* kt = smem + buf * 2 * TILE_BYTES;
+      const int left = nkeys - (ntiles - 1) * BK;  // 1..64 keys in the last tile
+      if (left == BK) {
+        step(false_type{}, true_type{}, sA, sB, kt, 0, kt, 1, 32);
+        step(false_type{}, false_type{}, sB, sA, kt, 1, kt, 0, 32);
+      } else {
+        step(true_type{}, true_type{}, sA, sB, kt, 0, kt, 1, left);
+        step(true_type{}, false_type{}, sB, sA, kt, 1, kt, 0, left - 32);
+      }
+    }
+  }
+
+  // ---- epilogue ----------------------------------------------------------------------------
+#pragma unroll
+  for (int qt = 0; qt < 2; ++qt) {
+    const float lt = ltil[qt] + __shfl_xor(ltil[qt], 32);
+    const float inv = lt > 0.f ? 1.0f / lt : 0.f;
+    const float l = ENT != 0 ? lsum[qt] + __shfl_xor(lsum[qt], 32) : lt;
+    const long long row = qrow0 + qrow[qt];
+    if (!SPLIT) {
+      if (ENT == 1) {
+        // App. B: H = log S - L / S; here in base-2 units, c_L = -H
+        float h = hsum[qt] + __shfl_xor(hsum[qt], 32);
+        float H2 = __log2f(l) - h / l;
+        if (qvalid[qt] && g == 0) P.cl[row] = -LN2 * H2;
+      }
+      if (ENT == 2) {
+        // sum_l R_l z_l = scale * aR . (sum_l R_l K_l): c_L = scale * (aR . alpha_L) - logsumexp
+        float dot = 0.f;
+        const bf16_t* qp = P.q + row * D;
+#pragma unroll
+        for (int ct = 0; ct < 4; ++ct)
+#pragma unroll
+          for (int c = 0; c < 4; ++c) {
+            uint2 w = *reinterpret_cast<const uint2*>(qp + 32 * ct + 8 * c + 4 * g);
+            dot += __uint_as_float(w.x << 16) * ok[qt][ct][4 * c + 0];
+            dot += __uint_as_float(w.x & 0xffff0000u) * ok[qt][ct][4 * c + 1];
+            dot += __uint_as_float(w.y << 16) * ok[qt][ct][4 * c + 2];
+            dot += __uint_as_float(w.y & 0xffff0000u) * ok[qt][ct][4 * c + 3];
+          }
+        dot += __shfl_xor(dot, 32);
+        float mean_t = dot * inv * sc[qt];          // sum_l R_l (s_l sc), log2 units
+        float lse2 = msc[qt] + __log2f(l);
+        if (qvalid[qt] && g == 0) P.cl[row] = LN2 * (mean_t - lse2);
+      }
+      if (qvalid[qt]) {
+#pragma unroll
+        for (int ct = 0; ct < 4; ++ct)
+#pragma unroll
+          for (int c = 0; c < 4; ++c) {
+            const int ch = 32 * ct + 8 * c + 4 * g;
+            if (OUT_K) {
+              uint2 w;
+              w.x = pack_bf16(ok[qt][ct][4 * c + 0] * inv, ok[qt][ct][4 * c + 1] * inv);
+              w.y = pack_bf16(ok[qt][ct][4 * c + 2] * inv, ok[qt][ct][4 * c + 3] * inv);
+              *reinterpret_cast<uint2*>(P.outk + row * D + ch) = w;
+            }
+            if (OUT_V) {
+              uint2 w;
+              w.x = pack_bf16(ov[qt][ct][4 * c + 0] * inv, ov[qt][ct][4 * c + 1] * inv);
+              w.y = pack_bf16(ov[qt][ct][4 * c + 2] * inv, ov[qt][ct][4 * c + 3] * inv);
+              *reinterpret_cast<uint2*>(P.outv + row * D + ch) = w;
+            }
+          }
+      }
+    } else {
+      // partial result of this key range: normalised output and log2-sum-exp
+      if (qvalid[qt]) {
+        const long long nprob = P.total_blocks / (P.nqb * P.nsplit);
+        const long long prow = ((long long)split * nprob + prob) * P.nq + qrow[qt];
+        if (g == 0) P.part_lse[prow] = lt > 0.f ? msc[qt] + __log2f(lt) : NEG_BIG;
+#pragma unroll
+        for (int ct = 0; ct < 4; ++ct)
+#pragma unroll
+          for (int c = 0; c < 4; ++c) {
+            const int ch = 32 * ct + 8 * c + 4 * g;
+            float4 w = {ov[qt][ct][4 * c + 0] * inv, ov[qt][ct][4 * c + 1] * inv, ov[qt][ct][4 * c + 2] * inv,
+                        ov[qt][ct][4 * c + 3] * inv};
+            *reinterpret_cast<float4*>(P.part_o + prow * D + ch) = w;
+          }
+      }
+    }
+  }
+}
+
+// Merge of the key-range partials of the first-frame recomputation: weights 2^(lse - max).
+__global__ void __launch_bounds__(128) merge_splits_kernel(const float* __restrict__ part_o,
+                                                           const float* __restrict__ part_lse, bf16_t* __restrict__ out,
+                                                           int nsplit, long long rows_per_split, int nq,
+                                                           long long out_rows_per_problem) {
+  const long long r = blockIdx.x;  // problem * nq + row
+  const int c = threadIdx.x;       // channel
+  const long long prob = r / nq;
+  const long long row = r - prob * nq;
+  float mx = -INFINITY;
+  for (int s = 0; s < nsplit; ++s) mx = fmaxf(mx, part_lse[s * rows_per_split + r]);
+  float wsum = 0.f, acc = 0.f;
+  for (int s = 0; s < nsplit; ++s) {
+    float w = exp2f(part_lse[s * rows_per_split + r] - mx);
+    wsum += w;
+    acc += w * part_o[(s * rows_per_split + r) * D + c];
+  }
+  out[(prob * out_rows_per_problem + row) * D + c] = f32_to_bf16(acc / wsum);
+}
+
+constexpr int FLASH_LDS_BYTES = 3 * 2 * TILE_BYTES;  // 96 KB
+
+template <bool OUT_K, bool OUT_V, int ENT, bool SPLIT>
+hipError_t launch_flash(const FlashParams& P, hipStream_t st) {
+  auto kern = flash_kernel<OUT_K, OUT_V, ENT, SPLIT>;
+  static bool configured = false;  // the attribute is per function, set once per process
+  if (!configured) {
+    hipError_t e = hipFuncSetAttribute((const void*)kern, hipFuncAttributeMaxDynamicSharedMemorySize, FLASH_LDS_BYTES);
+    if (e != hipSuccess) return e;
+    configured = true;
+  }
+  hipLaunchKernelGGL(kern, dim3(P.blocks_per_xcd * 8), dim3(256), FLASH_LDS_BYTES, st, P);
+  return hipGetLastError();
+}
+
+int first_frame_splits(const Dims& dm) {
+  const int nqb = (dm.b + BQ - 1) / BQ;
+  const long long tiles = (dm.N + BK - 1) / BK;
+  long long want = (4LL * 256 + (long long)dm.BH * nqb - 1) / ((long long)dm.BH * nqb);  // ~4 workgroups per CU
+  long long max_by_len = tiles / 8 > 0 ? tiles / 8 : 1;                                  // >= 8 tiles per split
+  long long s = want < max_by_len ? want : max_by_len;
+  if (s < 1) s = 1;
+  if (s > 64) s = 64;
+  const long long per = (tiles + s - 1) / s;  // tiles per split; drop splits that would be empty
+  s = (tiles + per - 1) / per;
+  return (int)s;
+}
+
+}  // namespace
+
+bool flash_supported(const Dims& dm) { return dm.d == D; }
+
+hipError_t launch_r_update_flash(const bf16_t* aR, const float* cR, const bf16_t* k, const bf16_t* v, bf16_t* aL,
+                                 float* cL, bf16_t* y, const Dims& dm, float row_scale, float cr_min, int entropy_mode,
+                                 hipStream_t st) {
+  FlashParams P = {};
+  P.q = aR; P.cR = cR; P.k = k; P.v = v; P.outk = aL; P.outv = y; P.cl = cL;
+  P.q_rows_per_problem = dm.b; P.k_rows_per_problem = dm.b;
+  P.nq = dm.b; P.nk = dm.b;
+  P.nqb = (dm.b + BQ - 1) / BQ;
+  P.nsplit = 1;
+  P.keys_per_split = ((dm.b + BK - 1) / BK) * BK;
+  long long total = (long long)dm.BH * dm.T * P.nqb;
+  if (total > 0x3fffffffLL) return hipErrorInvalidValue;
+  P.total_blocks = (int)total;
+  P.blocks_per_xcd = (P.total_blocks + 7) / 8;
+  P.row_scale = row_scale; P.cr_min = cr_min;
+  const bool ident = entropy_mode == VMONARCH_ENTROPY_IDENTITY;
+  // alpha_L and c_L from one pass over K; y = R V from a second pass that recomputes the
+  // logits.  A single pass with both accumulator sets needs all 256 accumulation registers
+  // for them and the compiler then spills heavily, which costs more than the repeated
+  // K Q^T product (one third of the fused pass's MFMA work).
+  hipError_t e = ident ? launch_flash<true, false, 2, false>(P, st) : launch_flash<true, false, 1, false>(P, st);
+  if (e != hipSuccess || v == nullptr) return e;
+  P.outk = nullptr;
+  P.cl = nullptr;
+  return launch_flash<false, true, 0, false>(P, st);
+}
+
+size_t first_frame_flash_scratch_bytes(const Dims& dm) {
+  const int ns = first_frame_splits(dm);
+  if (ns == 1) return 0;
+  size_t rows = (size_t)ns * dm.BH * dm.b;
+  return rows * D * sizeof(float) + ((rows * sizeof(float) + 255) & ~(size_t)255);
+}
+
+hipError_t launch_first_frame_flash(const bf16_t* q, const bf16_t* k, const bf16_t* v, bf16_t* out, void* scratch,
+                                    size_t scratch_bytes, const Dims& dm, hipStream_t st) {
+  FlashParams P = {};
+  const int ns = first_frame_splits(dm);
+  P.q = q; P.cR = nullptr; P.k = k; P.v = v; P.outk = nullptr; P.outv = out; P.cl = nullptr;
+  P.q_rows_per_problem = dm.N; P.k_rows_per_problem = dm.N;
+  P.nq = dm.b;
+  if (dm.N > 0x7fffffffLL - BK) return hipErrorInvalidValue;
+  P.nk = (int)dm.N;
+  P.nqb = (dm.b + BQ - 1) / BQ;
+  P.nsplit = ns;
+  const long long tiles = (dm.N + BK - 1) / BK;
+  P.keys_per_split = (int)(((tiles + ns - 1) / ns) * BK);
+  long long total = (long long)dm.BH * P.nqb * ns;
+  if (total > 0x3fffffffLL) return hipErrorInvalidValue;
+  P.total_blocks = (int)total;
+  P.blocks_per_xcd = (P.total_blocks + 7) / 8;
+  P.row_scale = 1.0f / sqrtf((float)dm.d);
+  P.cr_min = 0.f;
+  if (ns == 1) return launch_flash<false, true, 0, false>(P, st);
+  const size_t rows = (size_t)ns * dm.BH * dm.b;
+  const size_t need = rows * D * sizeof(float) + ((rows * sizeof(float) + 255) & ~(size_t)255);
+  if (scratch == nullptr || scratch_bytes < need) return hipErrorInvalidValue;
+  P.part_lse = (float*)scratch;
+  P.part_o = (float*)((char*)scratch + ((rows * sizeof(float) + 255) & ~(size_t)255));
+  hipError_t e = launch_flash<false, true, 0, true>(P, st);
+  if (e != hipSuccess) return e;
+  hipLaunchKernelGGL(merge_splits_kernel, dim3((unsigned)((long long)dm.BH * dm.b)), dim3(D), 0, st, P.part_o,
+                     P.part_lse, out, ns, (long long)dm.BH * dm.b, dm.b, dm.N);
+  return hipGetLastError();
+}
+
+}  // namespace vm

@@ -1,0 +1,290 @@
+// Plain-ALU kernels for spatio-temporal Monarch attention: any T, b and d <= 256, float or
+// bf16 tensors, float accumulation.  They serve the fp32 entry points and every bf16 shape
+// the MFMA kernels do not cover.  Written for clarity first; each follows the paper's
+// update equations directly (Sec. 3.1 Eqs. R / alpha_L, c_L / L / alpha_R, c_R; App. A).
+#include "common.h"
+
+namespace vm {
+
+namespace {
+
+constexpr int kMaxD = 256;
+
+struct EntState {  // App. B running state: max, sum exp(x-m), sum exp(x-m)(x-m)
+  float m, S, L;
+};
+
+__device__ __forceinline__ EntState ent_merge(EntState a, EntState c) {
+  // Combine two partial states; the rescale rule of App. B applied to both sides.
+  float mm = fmaxf(a.m, c.m);
+  EntState r;
+  r.m = mm;
+  float da = a.S > 0.f ? a.m - mm : 0.f;
+  float dc = c.S > 0.f ? c.m - mm : 0.f;
+  float ea = a.S > 0.f ? expf(da) : 0.f;
+  float ec = c.S > 0.f ? expf(dc) : 0.f;
+  r.S = a.S * ea + c.S * ec;
+  r.L = a.L * ea + a.S * ea * da + c.L * ec + c.S * ec * dc;
+  return r;
+}
+
+// One wave (64 lanes) per query row.  nk keys starting at kbase (and vbase) with row
+// stride d.  Emits out_k = softmax(z) K (if OUT_K), out_v = softmax(z) V (if OUT_V) and
+// cl = sum p log p (if cl != nullptr), with z = scale * (qrow . K[l]).
+template <typename E, bool OUT_K, bool OUT_V>
+__device__ void attend_row(const E* __restrict__ qrow, float scale, const E* __restrict__ kbase,
+                           const E* __restrict__ vbase, long long nk, int d, E* __restrict__ out_k,
+                           E* __restrict__ out_v, float* __restrict__ cl, float* sq, float* sp) {
+  const int lane = threadIdx.x;
+  for (int c = lane; c < d; c += 64) sq[c] = load_f<E>(qrow + c);
+  __syncthreads();
+  // pass 1: online (m, S, L) per lane over its keys, App. B recurrences
+  EntState st = {-INFINITY, 0.f, 0.f};
+  for (long long l = lane; l < nk; l += 64) {
+    const E* kr = kbase + l * d;
+    float z = 0.f;
+    for (int c = 0; c < d; ++c) z += sq[c] * load_f<E>(kr + c);
+    z *= scale;
+    float mn = fmaxf(st.m, z);
+    if (mn > st.m && st.S > 0.f) {
+      float dl = st.m - mn;
+      float al = expf(dl);
+      st.L = st.L * al + st.S * al * dl;
+      st.S = st.S * al;
+    }
+    float p = expf(z - mn);
+    st.S += p;
+    st.L += p * (z - mn);
+    st.m = mn;
+  }
+  for (int off = 32; off >= 1; off >>= 1) {
+    EntState o;
+    o.m = __shfl_xor(st.m, off);
+    o.S = __shfl_xor(st.S, off);
+    o.L = __shfl_xor(st.L, off);
+    st = ent_merge(st, o);
+  }
+  const float lse_shift = st.m;
+  const float inv_S = 1.f / st.S;
+  if (cl != nullptr && lane == 0) *cl = -(logf(st.S) - st.L * inv_S);  // c_L = -H
+  // pass 2: out = sum_l p_l row_l, 64 keys at a time through LDS
+  float acck[kMaxD / 64], accv[kMaxD / 64];
+#pragma unroll
+  for (int u = 0; u < kMaxD / 64; ++u) { acck[u] = 0.f; accv[u] = 0.f; }
+  for (long long l0 = 0; l0 < nk; l0 += 64) {
+    long long l = l0 + lane;
+    float p = 0.f;
+    if (l < nk) {
+      const E* kr = kbase + l * d;
+      float z = 0.f;
+      for (int c = 0; c < d; ++c) z += sq[c] * load_f<E>(kr + c);
+      p = expf(z * scale - lse_shift) * inv_S;
+    }
+    __syncthreads();
+    sp[lane] = p;
+    __syncthreads();
+    int cnt = (int)((nk - l0) < 64 ? (nk - l0) : 64);
+    for (int t = 0; t < cnt; ++t) {
+      float pt = sp[t];
+#pragma unroll
+      for (int u = 0; u < kMaxD / 64; ++u) {
+        int c = lane + 64 * u;
+        if (c < d) {
+          if (OUT_K) acck[u] += pt * load_f<E>(kbase + (l0 + t) * d + c);
+          if (OUT_V) accv[u] += pt * load_f<E>(vbase + (l0 + t) * d + c);
+        }
+      }
+    }
+  }
+#pragma unroll
+  for (int u = 0; u < kMaxD / 64; ++u) {
+    int c = lane + 64 * u;
+    if (c < d) {
+      if (OUT_K) store_f<E>(out_k + c, acck[u]);
+      if (OUT_V) store_f<E>(out_v + c, accv[u]);
+    }
+  }
+}
+
+template <typename E, bool HAS_V>
+__global__ void __launch_bounds__(64) r_update_generic_kernel(const E* __restrict__ aR, const float* __restrict__ cR,
+                                                              const E* __restrict__ k, const E* __restrict__ v,
+                                                              E* __restrict__ aL, float* __restrict__ cL,
+                                                              E* __restrict__ y, int T, int b, int d,
+                                                              float row_scale, float cr_min) {
+  __shared__ float sq[kMaxD];
+  __shared__ float sp[64];
+  const int i = blockIdx.x, kf = blockIdx.y, bh = blockIdx.z;
+  const long long row = ((long long)bh * T + kf) * b + i;
+  const long long frame0 = ((long long)bh * T + kf) * b;
+  float c = cR ? cR[row] : 1.f;
+  c = fmaxf(c, cr_min);
+  attend_row<E, true, HAS_V>(aR + row * d, row_scale / c, k + frame0 * d, HAS_V ? v + frame0 * d : nullptr, b, d,
+                             aL + row * d, HAS_V ? y + row * d : nullptr, cL + row, sq, sp);
+}
+
+template <typename E>
+__global__ void __launch_bounds__(64) first_frame_generic_kernel(const E* __restrict__ q, const E* __restrict__ k,
+                                                                 const E* __restrict__ v, E* __restrict__ out, int T,
+                                                                 int b, int d, float scale) {
+  __shared__ float sq[kMaxD];
+  __shared__ float sp[64];
+  const int i = blockIdx.x, bh = blockIdx.y;
+  const long long N = (long long)T * b;
+  const long long head0 = (long long)bh * N;
+  attend_row<E, false, true>(q + (head0 + i) * d, scale, k + head0 * d, v + head0 * d, N, d, nullptr,
+                             out + (head0 + i) * d, nullptr, sq, sp);
+}
+
+// One workgroup per (position i, batch*head).  The T x T block L_i lives in LDS.
+template <typename E, bool FINAL>
+__global__ void __launch_bounds__(256) l_update_generic_kernel(const E* __restrict__ q, const E* __restrict__ aL,
+                                                               const float* __restrict__ cL, const E* __restrict__ y,
+                                                               E* __restrict__ aR, float* __restrict__ cR,
+                                                               E* __restrict__ out, int T, int b, int d,
+                                                               float q_scale) {
+  extern __shared__ float Lm[];  // [T][T], Lm[j*T + k]
+  const int i = blockIdx.x, bh = blockIdx.y;
+  const long long head0 = (long long)bh * T * b;
+  const int tid = threadIdx.x;
+  // logits u[j,k] = q_scale * Q[j,i] . aL[k,i] - cL[k,i]
+  for (int e = tid; e < T * T; e += 256) {
+    int j = e / T, kf = e % T;
+    const E* qr = q + (head0 + (long long)j * b + i) * d;
+    const E* ar = aL + (head0 + (long long)kf * b + i) * d;
+    float s = 0.f;
+    for (int c = 0; c < d; ++c) s += load_f<E>(qr + c) * load_f<E>(ar + c);
+    Lm[e] = s * q_scale - cL[head0 + (long long)kf * b + i];
+  }
+  __syncthreads();
+  // row softmax over k
+  for (int j = tid; j < T; j += 256) {
+    float mx = -INFINITY;
+    for (int kf = 0; kf < T; ++kf) mx = fmaxf(mx, Lm[j * T + kf]);
+    float s = 0.f;
+    for (int kf = 0; kf < T; ++kf) {
+      float p = expf(Lm[j * T + kf] - mx);
+      Lm[j * T + kf] = p;
+      s += p;
+    }
+    float inv = 1.f / s;
+    for (int kf = 0; kf < T; ++kf) Lm[j * T + kf] *= inv;
+  }
+  __syncthreads();
+  if (FINAL) {
+    // out[j,i,:] = sum_k L[j,k] y[k,i,:]
+    for (int e = tid; e < T * d; e += 256) {
+      int j = e / d, c = e % d;
+      float s = 0.f;
+      for (int kf = 0; kf < T; ++kf) s += Lm[j * T + kf] * load_f<E>(y + (head0 + (long long)kf * b + i) * d + c);
+      store_f<E>(out + (head0 + (long long)j * b + i) * d + c, s);
+    }
+  } else {
+    // aR[k,i,:] = sum_j L[j,k] Q[j,i,:] ; cR[k,i] = sum_j L[j,k]
+    for (int e = tid; e < T * d; e += 256) {
+      int kf = e / d, c = e % d;
+      float s = 0.f;
+      for (int j = 0; j < T; ++j) s += Lm[j * T + kf] * load_f<E>(q + (head0 + (long long)j * b + i) * d + c);
+      store_f<E>(aR + (head0 + (long long)kf * b + i) * d + c, s);
+    }
+    for (int kf = tid; kf < T; kf += 256) {
+      float s = 0.f;
+      for (int j = 0; j < T; ++j) s += Lm[j * T + kf];
+      cR[head0 + (long long)kf * b + i] = s;
+    }
+  }
+}
+
+// Token-row permutation copy, 4-byte words.
+__global__ void __launch_bounds__(256) permute_tokens_kernel(const uint32_t* __restrict__ in, uint32_t* __restrict__ out,
+                                                             int T, int b, int row_words, int to_pos_major) {
+  const long long N = (long long)T * b;
+  const long long head0 = (long long)blockIdx.y * N;
+  const long long total = N * row_words;
+  for (long long e = (long long)blockIdx.x * 256 + threadIdx.x; e < total; e += (long long)gridDim.x * 256) {
+    long long p = e / row_words;   // destination row
+    int w = (int)(e % row_words);
+    long long src;
+    if (to_pos_major) {            // out[i*T + j] = in[j*b + i]
+      long long i = p / T, j = p % T;
+      src = j * b + i;
+    } else {                       // out[j*b + i] = in[i*T + j]
+      long long j = p / b, i = p % b;
+      src = i * T + j;
+    }
+    out[(head0 + p) * row_words + w] = in[(head0 + src) * row_words + w];
+  }
+}
+
+}  // namespace
+
+template <typename E>
+hipError_t launch_r_update_generic(const E* aR, const float* cR, const E* k, const E* v, E* aL, float* cL, E* y,
+                                   const Dims& dm, float row_scale, float cr_min, hipStream_t st) {
+  dim3 grid(dm.b, dm.T, dm.BH);
+  if (v != nullptr)
+    hipLaunchKernelGGL((r_update_generic_kernel<E, true>), grid, dim3(64), 0, st, aR, cR, k, v, aL, cL, y, dm.T, dm.b,
+                       dm.d, row_scale, cr_min);
+  else
+    hipLaunchKernelGGL((r_update_generic_kernel<E, false>), grid, dim3(64), 0, st, aR, cR, k, v, aL, cL, y, dm.T,
+                       dm.b, dm.d, row_scale, cr_min);
+  return hipGetLastError();
+}
+
+template <typename E>
+hipError_t launch_l_update_generic(const E* q, const E* aL, const float* cL, const E* y, E* aR, float* cR, E* out,
+                                   const Dims& dm, float q_scale, hipStream_t st) {
+  dim3 grid(dm.b, dm.BH);
+  size_t lds = (size_t)dm.T * dm.T * sizeof(float);
+  hipError_t e;
+  if (y != nullptr) {
+    auto kern = l_update_generic_kernel<E, true>;
+    if (lds > 48 * 1024) {
+      e = hipFuncSetAttribute((const void*)kern, hipFuncAttributeMaxDynamicSharedMemorySize, (int)lds);
+      if (e != hipSuccess) return e;
+    }
+    hipLaunchKernelGGL(kern, grid, dim3(256), lds, st, q, aL, cL, y, aR, cR, out, dm.T, dm.b, dm.d, q_scale);
+  } else {
+    auto kern = l_update_generic_kernel<E, false>;
+    if (lds > 48 * 1024) {
+      e = hipFuncSetAttribute((const void*)kern, hipFuncAttributeMaxDynamicSharedMemorySize, (int)lds);
+      if (e != hipSuccess) return e;
+    }
+    hipLaunchKernelGGL(kern, grid, dim3(256), lds, st, q, aL, cL, y, aR, cR, out, dm.T, dm.b, dm.d, q_scale);
+  }
+  return hipGetLastError();
+}
+
+template <typename E>
+hipError_t launch_first_frame_generic(const E* q, const E* k, const E* v, E* out, const Dims& dm, hipStream_t st) {
+  dim3 grid(dm.b, dm.BH);
+  hipLaunchKernelGGL((first_frame_generic_kernel<E>), grid, dim3(64), 0, st, q, k, v, out, dm.T, dm.b, dm.d,
+                     1.0f / sqrtf((float)dm.d));
+  return hipGetLastError();
+}
+
+hipError_t launch_permute_tokens(const void* in, void* out, const Dims& dm, int row_bytes, int to_pos_major,
+                                 hipStream_t st) {
+  long long total = dm.N * (row_bytes / 4);
+  long long blocks = (total + 255) / 256;
+  if (blocks > 4096) blocks = 4096;
+  dim3 grid((unsigned)blocks, dm.BH);
+  hipLaunchKernelGGL(permute_tokens_kernel, grid, dim3(256), 0, st, (const uint32_t*)in, (uint32_t*)out, dm.T, dm.b,
+                     row_bytes / 4, to_pos_major);
+  return hipGetLastError();
+}
+
+template hipError_t launch_r_update_generic<float>(const float*, const float*, const float*, const float*, float*,
+                                                   float*, float*, const Dims&, float, float, hipStream_t);
+template hipError_t launch_r_update_generic<bf16_t>(const bf16_t*, const float*, const bf16_t*, const bf16_t*, bf16_t*,
+                                                    float*, bf16_t*, const Dims&, float, float, hipStream_t);
+template hipError_t launch_l_update_generic<float>(const float*, const float*, const float*, const float*, float*,
+                                                   float*, float*, const Dims&, float, hipStream_t);
+template hipError_t launch_l_update_generic<bf16_t>(const bf16_t*, const bf16_t*, const float*, const bf16_t*, bf16_t*,
+                                                    float*, bf16_t*, const Dims&, float, hipStream_t);
+template hipError_t launch_first_frame_generic<float>(const float*, const float*, const float*, float*, const Dims&,
+                                                      hipStream_t);
+template hipError_t launch_first_frame_generic<bf16_t>(const bf16_t*, const bf16_t*, const bf16_t*, bf16_t*,
+                                                       const Dims&, hipStream_t);
+
+}  // namespace vm

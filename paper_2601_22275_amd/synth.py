@@ -109,7 +109,8 @@ def head_inputs(T, Hs, Ws, d, config, head, gain=None, sink=0.0, phi=None):
         pa = rng.integers(0, N, size=65536)
         pb = rng.integers(0, N, size=65536)
         logits = np.einsum("nd,nd->n", q[pa].astype(np.float64), k[pb].astype(np.float64)) / math.sqrt(d)
-        gain = math.sqrt(3.0 / float(logits.std()))
+        sd = float(logits.std())
+        gain = math.sqrt(3.0 / sd) if sd > 1e-6 else 1.0   # a single token has no spread to normalise
     q *= np.float32(gain)
     k *= np.float32(gain)
     return q, k, v, float(gain)
