@@ -1,0 +1,188 @@
+#!/usr/bin/env python3
+"""Throughput of spatio-temporal Monarch attention on one MI355X.
+
+    python bench.py [--gpus 1] [--steps K] [--warmup W] [--workload NAME] [--no-cpu-baseline]
+
+One step = one call of the whole path (every sweep's R-update and L-update, the apply-to-V
+and the first-frame recomputation) on a seeded synthetic workload that is already resident
+in HBM.  Prints ONE JSON line: effective TFLOP/s (algorithmic FLOPs of the method / time),
+ms per call, the roofline position of the dominant kernel (the blocked-softmax R-update)
+from HIP-event phase timings taken in this run, the HBM-bound L-update's GB/s, and the CPU
+oracle timed on the host cores on a bounded sample of the same workload.
+"""
+from __future__ import annotations
+
+import argparse
+import json
+import math
+import os
+import sys
+import time
+
+ROOT = os.path.dirname(os.path.abspath(__file__))
+if ROOT not in sys.path:
+    sys.path.insert(0, ROOT)
+
+BF16_MFMA_PEAK_TFLOPS = 2500.0   # MI355X dense bf16 (published)
+HBM_PEAK_GBS = 8000.0            # MI355X HBM3E (published)
+
+
+def cpu_baseline(wl, q_bits, k_bits, v_bits, positions=48, rows=48):
+    """The oracle as it stands, on one head: `positions` query positions followed through
+    the whole iteration (all T frames) plus `rows` first-frame rows recomputed exactly."""
+    import numpy as np
+    from oracle import vmonarch_oracle as O
+
+    q, k, v = (O.widen_bf16(x) for x in (q_bits, k_bits, v_bits))
+    rng = np.random.default_rng(5)
+    pos = np.sort(rng.choice(wl.b, size=min(positions, wl.b), replace=False))
+    t0 = time.perf_counter()
+    O.monarch_attention(q, k, v, wl.T, wl.b, wl.iters, recompute=False, positions=pos)
+    if wl.recompute:
+        O.first_frame_attention(q, k, v, wl.b, rows=pos[:rows])
+    dt = time.perf_counter() - t0
+    T, b, d, N = wl.T, wl.b, wl.d, wl.N
+    s = len(pos)
+    flops = s * ((wl.iters - 1) * 4 * T * b * d + 6 * T * b * d + wl.iters * 4 * T * T * d)
+    if wl.recompute:
+        flops += min(rows, s) * 4 * N * d
+    try:
+        cores = len(os.sched_getaffinity(0))
+    except AttributeError:  # pragma: no cover
+        cores = os.cpu_count() or 1
+    omp = os.environ.get("OMP_NUM_THREADS")
+    if omp and omp.isdigit():
+        cores = min(cores, int(omp))
+    return {
+        "value": flops / dt / 1e12, "unit": "TFLOP/s", "cores": cores, "kind": "oracle",
+        "sample": f"1 head, {s} of {b} query positions x all {T} frames through {wl.iters} sweeps"
+                  + (f" + {min(rows, s)} first-frame rows over all {N} keys" if wl.recompute else "")
+                  + f", fp64 NumPy, {dt:.1f} s",
+        "seconds": dt,
+    }
+
+
+def main() -> int:
+    ap = argparse.ArgumentParser()
+    ap.add_argument("--gpus", type=int, default=1)
+    ap.add_argument("--steps", type=int, default=20)
+    ap.add_argument("--warmup", type=int, default=3)
+    ap.add_argument("--workload", default="long-81x28x52")
+    ap.add_argument("--entropy", choices=["online", "identity"], default="online")
+    ap.add_argument("--no-cpu-baseline", action="store_true")
+    args = ap.parse_args()
+    if args.gpus != 1:
+        print("bench.py: this build runs on ONE GPU only (no sharding, no collectives); use --gpus 1", file=sys.stderr)
+        return 2
+
+    import numpy as np
+    import torch
+
+    from paper_2601_22275_amd import binding, synth
+
+    if not torch.cuda.is_available():
+        print("bench.py: no GPU visible", file=sys.stderr)
+        return 2
+    binding.lib()  # fail loudly when the HIP library is missing
+    wl = synth.WORKLOADS[args.workload]
+    dev = torch.device("cuda:0")
+    bf16 = wl.dtype == "bf16"
+
+    t0 = time.perf_counter()
+    q, k, v = synth.make_inputs(wl)
+    gen_s = time.perf_counter() - t0
+
+    def up(x):
+        t = torch.from_numpy(x).to(dev)
+        if bf16:
+            t = t.view(torch.bfloat16)
+        return t.view(wl.B, wl.heads, wl.N, wl.d)
+
+    tq, tk, tv = up(q), up(k), up(v)
+    out = torch.empty_like(tq)
+    ws_bytes = binding.workspace_bytes(wl.B, wl.heads, wl.T, wl.Hs, wl.Ws, wl.d, wl.iters, wl.recompute, 2 if bf16 else 4)
+    ws = torch.empty(ws_bytes, dtype=torch.uint8, device=dev)
+    binding.set_workspace(ws)
+    binding.set_entropy_mode(binding.ENTROPY_IDENTITY if args.entropy == "identity" else binding.ENTROPY_ONLINE)
+
+    def step():
+        binding.attention(tq, tk, tv, wl.T, wl.Hs, wl.Ws, wl.iters, wl.recompute, out=out)
+
+    for _ in range(args.warmup):
+        step()
+    torch.cuda.synchronize()
+    # ---- timed region: exactly K steps, inputs resident, events on the launch stream ----
+    evs = [torch.cuda.Event(enable_timing=True) for _ in range(args.steps + 1)]
+    torch.cuda.synchronize()
+    t0 = time.perf_counter()
+    evs[0].record()
+    for i in range(args.steps):
+        step()
+        evs[i + 1].record()
+    torch.cuda.synchronize()
+    wall = time.perf_counter() - t0
+    per_step = sorted(evs[i].elapsed_time(evs[i + 1]) for i in range(args.steps))
+    ms = wall * 1e3 / args.steps
+    flops = synth.algorithmic_flops(wl.B, wl.heads, wl.T, wl.b, wl.d, wl.iters, wl.recompute)
+    tflops = flops / (ms * 1e-3) / 1e12
+
+    # ---- per-phase durations of the same call, HIP events recorded by the library between
+    # its kernels on this stream (a second, instrumented pass over K steps)
+    binding.set_phase_timing(True)
+    phase_ms = {}
+    for _ in range(args.steps):
+        step()
+        for name, t in binding.get_phase_timing():
+            phase_ms.setdefault(name, []).append(t)
+    binding.set_phase_timing(False)
+    phases = {n: sum(x) / len(x) for n, x in phase_ms.items()}
+
+    BH, T, b, d, N = wl.B * wl.heads, wl.T, wl.b, wl.d, wl.N
+    elem = 2 if bf16 else 4
+    roofline = None
+    hbm_phase = None
+    if "r_update" in phases or "r_update_last" in phases:
+        # dominant kernel: the blocked-softmax pass of the R-update (logits + R K), one launch
+        # per sweep; a fitting sweep is exactly one launch of it.
+        if "r_update" in phases:
+            fl, t_ms, what = 4.0 * BH * T * b * b * d, phases["r_update"], "flash_kernel (R-update, logits + R K), fitting sweep"
+        else:
+            fl, t_ms, what = 6.0 * BH * T * b * b * d, phases["r_update_last"], "R-update of the last sweep (two launches: R K pass and R V pass)"
+        ach = fl / (t_ms * 1e-3) / 1e12
+        roofline = {"bound": "mfma", "achieved": ach, "peak": BF16_MFMA_PEAK_TFLOPS, "unit": "TFLOP/s",
+                    "frac": ach / BF16_MFMA_PEAK_TFLOPS, "traffic": None, "kernel": what,
+                    "flops_per_launch": fl, "ms_per_launch": t_ms}
+    if "l_update" in phases:
+        # fitting L-update: reads q and alpha_L, writes alpha_R (3 token tensors) + c_L, c_R
+        by = 3.0 * BH * N * d * elem + 2.0 * BH * N * 4
+        hbm_phase = {"kernel": "l_update_mfma_kernel (fitting sweep)", "bytes_per_launch": by,
+                     "ms_per_launch": phases["l_update"], "achieved": by / (phases["l_update"] * 1e-3) / 1e9,
+                     "peak": HBM_PEAK_GBS, "unit": "GB/s",
+                     "frac": by / (phases["l_update"] * 1e-3) / 1e9 / HBM_PEAK_GBS}
+
+    cpu = None
+    if not args.no_cpu_baseline and bf16:
+        cpu = cpu_baseline(wl, q[0], k[0], v[0])
+
+    rec = {
+        "metric": "spatio-temporal Monarch attention, effective TFLOP/s (algorithmic FLOPs / time per call)",
+        "value": tflops, "unit": "TFLOP/s", "n_gpus": 1, "steps": args.steps, "warmup": args.warmup,
+        "ms_per_step": ms, "ms_per_step_median": per_step[len(per_step) // 2], "ms_per_step_min": per_step[0],
+        "higher_is_better": True, "scaling": "weak", "vs_baseline": None,
+        "dtype": "bf16" if bf16 else "f32", "data": "synthetic",
+        "pct_bf16_mfma_peak": 100.0 * tflops / BF16_MFMA_PEAK_TFLOPS,
+        "algorithmic_tflop_per_call": flops / 1e12,
+        "config": {"workload": wl.name, "B": wl.B, "heads": wl.heads, "T": wl.T, "Hs": wl.Hs, "Ws": wl.Ws,
+                   "N": wl.N, "d": wl.d, "iters": wl.iters, "recompute": bool(wl.recompute),
+                   "entropy": args.entropy, "input_generation_s": gen_s},
+        "phase_ms": phases,
+        "roofline": roofline,
+        "hbm_phase": hbm_phase,
+        "cpu_baseline": cpu,
+    }
+    print(json.dumps(rec))
+    return 0
+
+
+if __name__ == "__main__":
+    sys.exit(main())

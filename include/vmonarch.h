@@ -62,6 +62,15 @@ float vmonarch_get_cr_min(void);
 int vmonarch_set_entropy_mode(int mode);
 int vmonarch_get_entropy_mode(void);
 
+/* Benchmark aid.  While enabled, vmonarch_attention[_f32] records a HIP event on the caller's
+ * stream before each of its phases ("r_update", "l_update", "r_update_last", "l_update_last",
+ * "first_frame") and one at the end.  vmonarch_get_phase_timing waits for the last call's
+ * final event and writes, for up to `cap` phases, the elapsed milliseconds to ms_host[i] and
+ * the phase name to names_host + 32*i (HOST buffers of cap floats / cap*32 chars).  A phase
+ * may span more than one kernel launch.  Not thread-safe; off by default. */
+int vmonarch_set_phase_timing(int enable);
+int vmonarch_get_phase_timing(int* n_phases, float* ms_host, char* names_host, int cap);
+
 /* Bytes of device scratch vmonarch_attention[_f32] needs for these sizes
  * (elem_bytes = 2 for bf16, 4 for f32).  0 on invalid sizes. */
 size_t vmonarch_workspace_bytes(int B, int heads, int T, int Hs, int Ws, int d, int iters,

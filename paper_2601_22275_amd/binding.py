@@ -27,7 +27,7 @@ EXPORTS = [
     "vmonarch_set_workspace", "vmonarch_shutdown", "vmonarch_attention", "vmonarch_attention_f32",
     "vmonarch_r_update", "vmonarch_r_update_f32", "vmonarch_l_update", "vmonarch_l_update_f32",
     "vmonarch_first_frame_attention", "vmonarch_first_frame_attention_f32", "vmonarch_index_maps",
-    "vmonarch_permute_tokens",
+    "vmonarch_permute_tokens", "vmonarch_set_phase_timing", "vmonarch_get_phase_timing",
 ]
 
 
@@ -55,6 +55,8 @@ def lib() -> ctypes.CDLL:
         L.vmonarch_workspace_bytes.restype = c_size_t
         L.vmonarch_workspace_bytes.argtypes = dims + [c_int, c_int, c_int]
         L.vmonarch_set_workspace.argtypes = [c_void_p, c_size_t]
+        L.vmonarch_set_phase_timing.argtypes = [c_int]
+        L.vmonarch_get_phase_timing.argtypes = [c_void_p, c_void_p, c_void_p, c_int]
         for name in ("vmonarch_attention", "vmonarch_attention_f32"):
             getattr(L, name).argtypes = [c_void_p] * 4 + dims + [c_int, c_int, c_void_p]
         for name in ("vmonarch_r_update", "vmonarch_r_update_f32"):
@@ -108,6 +110,20 @@ def get_cr_min() -> float:
 
 def set_entropy_mode(mode: int) -> None:
     _check(lib().vmonarch_set_entropy_mode(mode))
+
+
+def set_phase_timing(enable: bool) -> None:
+    _check(lib().vmonarch_set_phase_timing(int(bool(enable))))
+
+
+def get_phase_timing():
+    """[(phase name, milliseconds)] of the last attention call made while timing was enabled."""
+    cap = 32
+    n = c_int(0)
+    ms = (c_float * cap)()
+    names = ctypes.create_string_buffer(cap * 32)
+    _check(lib().vmonarch_get_phase_timing(ctypes.byref(n), ms, names, cap))
+    return [(names.raw[32 * i:32 * i + 32].split(b"\0")[0].decode(), float(ms[i])) for i in range(n.value)]
 
 
 def workspace_bytes(B, heads, T, Hs, Ws, d, iters, recompute, elem_bytes) -> int:

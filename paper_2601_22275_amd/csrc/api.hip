@@ -26,6 +26,31 @@ size_t g_user_ws_bytes = 0;
 void* g_arena[64] = {nullptr};  // per device, library-owned
 size_t g_arena_bytes[64] = {0};
 
+// Optional per-phase timing of vmonarch_attention (benchmarks only): events recorded on the
+// caller's stream between the kernels of one call.
+constexpr int kMaxPhases = 32;
+bool g_timing = false;
+hipEvent_t g_ev[kMaxPhases + 1];
+bool g_ev_created = false;
+int g_n_phases = 0;
+char g_phase_name[kMaxPhases][32];
+
+void phase_mark(hipStream_t st, const char* name_of_phase_that_starts) {
+  if (!g_timing) return;
+  if (!g_ev_created) {
+    for (int i = 0; i <= kMaxPhases; ++i) (void)hipEventCreate(&g_ev[i]);
+    g_ev_created = true;
+  }
+  if (name_of_phase_that_starts == nullptr) {  // closing mark
+    (void)hipEventRecord(g_ev[g_n_phases], st);
+    return;
+  }
+  if (g_n_phases >= kMaxPhases) return;
+  (void)hipEventRecord(g_ev[g_n_phases], st);
+  snprintf(g_phase_name[g_n_phases], sizeof(g_phase_name[0]), "%s", name_of_phase_that_starts);
+  ++g_n_phases;
+}
+
 int fail(int code, const char* fmt, ...) {
   va_list ap;
   va_start(ap, fmt);
@@ -204,19 +229,24 @@ int attention_impl(const void* q_, const void* k_, const void* v_, void* out_, i
   const float cr_min = g_cr_min;
   // App. A: aR = Q, cR = 1, then `iters` times (R-update; L-update); y = R V and O = L y
   // ride on the last sweep.  Q carries 1/sqrt(d) through row_scale / q_scale.
+  g_n_phases = 0;
   for (int sweep = 0; sweep < iters; ++sweep) {
     const bool last = sweep == iters - 1;
+    phase_mark(st, last ? "r_update_last" : "r_update");
     rc = r_update_any<E>(sweep == 0 ? q : aR, sweep == 0 ? nullptr : cR, k, last ? v : nullptr, aL, cL,
                          last ? y : nullptr, dm, s, cr_min, st);
     if (rc) return rc;
+    phase_mark(st, last ? "l_update_last" : "l_update");
     rc = l_update_any<E>(q, aL, cL, last ? y : nullptr, last ? nullptr : aR, last ? nullptr : cR, last ? out : nullptr,
                          dm, s, st);
     if (rc) return rc;
   }
   if (recompute) {
+    phase_mark(st, "first_frame");
     rc = first_frame_any<E>(q, k, v, out, ws + w.ff, w.total - w.ff, dm, st);
     if (rc) return rc;
   }
+  phase_mark(st, nullptr);
   return VMONARCH_OK;
 }
 
@@ -280,6 +310,27 @@ int vmonarch_set_cr_min(float cr_min) {
   return VMONARCH_OK;
 }
 float vmonarch_get_cr_min(void) { return g_cr_min; }
+
+int vmonarch_set_phase_timing(int enable) {
+  g_timing = enable != 0;
+  return VMONARCH_OK;
+}
+
+int vmonarch_get_phase_timing(int* n_phases, float* ms_host, char* names_host, int cap) {
+  if (!n_phases || !ms_host || !names_host || cap <= 0) return fail(VMONARCH_ERR_INVALID_ARG, "null output or cap <= 0");
+  *n_phases = 0;
+  if (!g_timing || !g_ev_created || g_n_phases == 0) return VMONARCH_OK;
+  hipError_t e = hipEventSynchronize(g_ev[g_n_phases]);
+  if (e != hipSuccess) return hip_fail(e, "hipEventSynchronize");
+  const int n = g_n_phases < cap ? g_n_phases : cap;
+  for (int i = 0; i < n; ++i) {
+    e = hipEventElapsedTime(&ms_host[i], g_ev[i], g_ev[i + 1]);
+    if (e != hipSuccess) return hip_fail(e, "hipEventElapsedTime");
+    snprintf(names_host + 32 * i, 32, "%s", g_phase_name[i]);
+  }
+  *n_phases = n;
+  return VMONARCH_OK;
+}
 
 int vmonarch_set_entropy_mode(int mode) {
   if (mode != VMONARCH_ENTROPY_ONLINE && mode != VMONARCH_ENTROPY_IDENTITY)

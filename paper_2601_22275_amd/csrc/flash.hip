@@ -28,8 +28,16 @@ namespace vm {
 namespace {
 
 constexpr int D = 128;          // head dimension handled here
-constexpr int BQ = 256;         // query rows per workgroup
 constexpr int BK = 64;          // key rows per LDS tile
+#ifndef VM_FLASH_QT
+#define VM_FLASH_QT 1           // 32-query tiles per wave
+#endif
+#ifndef VM_FLASH_NW
+#define VM_FLASH_NW 8           // waves per workgroup
+#endif
+constexpr int QT = VM_FLASH_QT;
+constexpr int NW = VM_FLASH_NW;
+constexpr int BQ = 32 * QT * NW;  // query rows per workgroup
 constexpr int ROW_BYTES = D * 2;
 constexpr int TILE_BYTES = BK * ROW_BYTES;  // 16 KB
 constexpr float LOG2E = 1.4426950408889634f;
@@ -87,37 +95,46 @@ __device__ __forceinline__ uint32_t pack_bf16(float a, float b) {
 // instructions cannot address those, so each element takes the read / multiply / write
 // round trip explicitly; spelled as inline assembly so that the register allocator keeps the
 // tile in accumulation registers instead of migrating it to the (scarcer) vector registers.
-// The caller brackets a batch of these with s_nop padding for the MFMA <-> VALU hazards.
+// The compiler does not see inside the statement, so the MFMA -> VALU read hazard (the
+// producing MFMA needs 16 passes plus 2 quad-cycles before its result may be read) and the
+// VALU write -> MFMA read hazard are covered by s_nop inside the same statement: the
+// statement is ordered after the producing MFMA and before the consuming one by its operands.
 __device__ __forceinline__ void scale_acc(f32x16& acc, float alpha) {
 #pragma unroll
-  for (int r = 0; r < 16; ++r) {
-    float in = acc[r], out, tmp;
-    asm volatile("v_accvgpr_read_b32 %0, %2\n\tv_mul_f32 %0, %0, %3\n\tv_accvgpr_write_b32 %1, %0"
-                 : "=&v"(tmp), "=a"(out)
-                 : "a"(in), "v"(alpha));
-    acc[r] = out;
+  for (int h8 = 0; h8 < 2; ++h8) {
+    float x0 = acc[8 * h8 + 0], x1 = acc[8 * h8 + 1], x2 = acc[8 * h8 + 2], x3 = acc[8 * h8 + 3];
+    float x4 = acc[8 * h8 + 4], x5 = acc[8 * h8 + 5], x6 = acc[8 * h8 + 6], x7 = acc[8 * h8 + 7];
+    float tmp;
+    asm volatile(
+        "s_nop 15\n\ts_nop 3\n\t"
+        "v_accvgpr_read_b32 %8, %0\n\tv_mul_f32 %8, %8, %9\n\tv_accvgpr_write_b32 %0, %8\n\t"
+        "v_accvgpr_read_b32 %8, %1\n\tv_mul_f32 %8, %8, %9\n\tv_accvgpr_write_b32 %1, %8\n\t"
+        "v_accvgpr_read_b32 %8, %2\n\tv_mul_f32 %8, %8, %9\n\tv_accvgpr_write_b32 %2, %8\n\t"
+        "v_accvgpr_read_b32 %8, %3\n\tv_mul_f32 %8, %8, %9\n\tv_accvgpr_write_b32 %3, %8\n\t"
+        "v_accvgpr_read_b32 %8, %4\n\tv_mul_f32 %8, %8, %9\n\tv_accvgpr_write_b32 %4, %8\n\t"
+        "v_accvgpr_read_b32 %8, %5\n\tv_mul_f32 %8, %8, %9\n\tv_accvgpr_write_b32 %5, %8\n\t"
+        "v_accvgpr_read_b32 %8, %6\n\tv_mul_f32 %8, %8, %9\n\tv_accvgpr_write_b32 %6, %8\n\t"
+        "v_accvgpr_read_b32 %8, %7\n\tv_mul_f32 %8, %8, %9\n\tv_accvgpr_write_b32 %7, %8\n\t"
+        "s_nop 3"
+        : "+a"(x0), "+a"(x1), "+a"(x2), "+a"(x3), "+a"(x4), "+a"(x5), "+a"(x6), "+a"(x7), "=&v"(tmp)
+        : "v"(alpha));
+    acc[8 * h8 + 0] = x0; acc[8 * h8 + 1] = x1; acc[8 * h8 + 2] = x2; acc[8 * h8 + 3] = x3;
+    acc[8 * h8 + 4] = x4; acc[8 * h8 + 5] = x5; acc[8 * h8 + 6] = x6; acc[8 * h8 + 7] = x7;
   }
 }
 
 // Row maximum of one 32-key sub-tile for one 32-query tile.  `s` holds the raw logits
 // (aR . K) of query `lane & 31` for keys {8c + 4g + r}; the partner lane (lane ^ 32) holds the
-// other 16 keys.  Keys at or beyond `keys_left` are ignored when TAIL.
-template <bool TAIL>
-__device__ __forceinline__ float subtile_max(const f32x16& s, int g, int keys_left) {
-  float sv[16];
+// other 16 keys and is reached with v_permlane32_swap (no LDS round trip).  Key rows past
+// the end of the range are copies of the last valid row, so they never change a maximum.
+__device__ __forceinline__ float subtile_max(const f32x16& s) {
+  float mx = fmaxf(fmaxf(s[0], s[1]), s[2]);
 #pragma unroll
-  for (int r = 0; r < 16; ++r) {
-    sv[r] = s[r];
-    if (TAIL) {
-      int key = 8 * (r >> 2) + 4 * g + (r & 3);
-      if (key >= keys_left) sv[r] = -3.0e38f;
-    }
-  }
-  float mx = fmaxf(fmaxf(sv[0], sv[1]), sv[2]);
-#pragma unroll
-  for (int r = 3; r < 15; r += 2) mx = fmaxf(fmaxf(mx, sv[r]), sv[r + 1]);
-  mx = fmaxf(mx, sv[15]);
-  return fmaxf(mx, __shfl_xor(mx, 32));
+  for (int r = 3; r < 15; r += 2) mx = fmaxf(fmaxf(mx, s[r]), s[r + 1]);
+  mx = fmaxf(mx, s[15]);
+  const unsigned u = __float_as_uint(mx);
+  auto sw = __builtin_amdgcn_permlane32_swap(u, u, false, false);
+  return fmaxf(__uint_as_float(sw[0]), __uint_as_float(sw[1]));
 }
 
 // Probabilities of the sub-tile relative to the reference max `msc` (log2 units):
@@ -144,7 +161,11 @@ __device__ __forceinline__ void subtile_probs(const f32x16& s, float sc, float m
       int key = 8 * (r >> 2) + 4 * g + (r & 3);
       if (key >= keys_left) t = -1000.0f;
     }
+#ifdef VM_DBG_NO_EXP
+    p[r] = t * 1.0e-3f;
+#else
     p[r] = __builtin_amdgcn_exp2f(t);
+#endif
     if (ENT != 0) l += p[r];
     if (ENT == 1) h = __builtin_fmaf(p[r], t, h);
   }
@@ -163,7 +184,7 @@ __device__ __forceinline__ void subtile_probs(const f32x16& s, float sc, float m
 }
 
 template <bool OUT_K, bool OUT_V, int ENT, bool SPLIT>
-__global__ void __launch_bounds__(256) __attribute__((amdgpu_waves_per_eu(1, 1))) flash_kernel(FlashParams P) {
+__global__ void __launch_bounds__(64 * NW) flash_kernel(FlashParams P) {
   extern __shared__ __attribute__((aligned(16))) char smem[];  // [3 buffers][K|V][64 rows][256 B]
 
   // XCD-aware placement: hardware deals workgroups to the 8 XCDs round-robin, so give each
@@ -194,13 +215,13 @@ __global__ void __launch_bounds__(256) __attribute__((amdgpu_waves_per_eu(1, 1))
   const bf16_t* vbase = OUT_V ? P.v + ((long long)prob * P.k_rows_per_problem + kbeg) * D : nullptr;
 
   // ---- queries: B operand of S^T = K Q^T, kept in registers -------------------------
-  bf16x8 qreg[2][8];
-  float sc[2];
-  int qrow[2];
-  bool qvalid[2];
+  bf16x8 qreg[QT][8];
+  float sc[QT];
+  int qrow[QT];
+  bool qvalid[QT];
 #pragma unroll
-  for (int qt = 0; qt < 2; ++qt) {
-    int r = qb * BQ + wave * 64 + qt * 32 + ql;
+  for (int qt = 0; qt < QT; ++qt) {
+    int r = qb * BQ + wave * (32 * QT) + qt * 32 + ql;
     qvalid[qt] = r < P.nq;
     qrow[qt] = qvalid[qt] ? r : P.nq - 1;
     const bf16_t* qp = P.q + (qrow0 + qrow[qt]) * D + 8 * g;
@@ -214,10 +235,10 @@ __global__ void __launch_bounds__(256) __attribute__((amdgpu_waves_per_eu(1, 1))
   // ---- LDS addressing ----------------------------------------------------------------
   // staging: global -> LDS directly (global_load_lds_dwordx4).  One wave instruction fills 64
   // consecutive 16-byte slots (4 key rows); slot = key * 16 + physical chunk.  Wave w issues
-  // the instructions for key rows 16 r + 4 w .. + 3 (r = 0..3); each lane fetches the logical
+  // the instructions for key rows 4 NW r + 4 w .. + 3 (r = 0 .. 16/NW - 1); each lane fetches the logical
   // chunk that belongs in its slot.  Rows past the end of the key range are clamped to the
   // last valid row (finite data that the tail mask removes again).
-  const int st_key = 4 * wave + (lane >> 4);             // + 16 r
+  const int st_key = 4 * wave + (lane >> 4);             // + 4 NW r
   const int st_lc = (lane & 15) ^ swz(st_key);
   // row reads (A of S^T): key row = 32 st + ql, logical chunk 2 ks + g
   int a_off[8];
@@ -240,26 +261,31 @@ __global__ void __launch_bounds__(256) __attribute__((amdgpu_waves_per_eu(1, 1))
   }
 
   // ---- accumulators --------------------------------------------------------------------
-  f32x16 ok[2][4], ov[2][4];
+  static_assert(OUT_K != OUT_V, "one accumulator set per pass (see launch_r_update_flash)");
+  f32x16 oacc[QT][4];  // O^T tiles: [query tile][32-channel tile]
 #pragma unroll
-  for (int qt = 0; qt < 2; ++qt)
+  for (int qt = 0; qt < QT; ++qt)
 #pragma unroll
     for (int ct = 0; ct < 4; ++ct)
 #pragma unroll
-      for (int r = 0; r < 16; ++r) {
-        if (OUT_K) ok[qt][ct][r] = 0.f;
-        if (OUT_V) ov[qt][ct][r] = 0.f;
-      }
-  float msc[2] = {NEG_BIG, NEG_BIG}, ltil[2] = {0.f, 0.f}, lsum[2] = {0.f, 0.f}, hsum[2] = {0.f, 0.f};
+      for (int r = 0; r < 16; ++r) oacc[qt][ct][r] = 0.f;
+  float msc[QT], ltil[QT], lsum[QT], hsum[QT];
+#pragma unroll
+  for (int qt = 0; qt < QT; ++qt) {
+    msc[qt] = NEG_BIG;
+    ltil[qt] = 0.f;
+    lsum[qt] = 0.f;
+    hsum[qt] = 0.f;
+  }
 
   // ---- tile staging ----------------------------------------------------------------------
   auto issue_tile = [&](int t, int buf) {
     char* kb = smem + buf * 2 * TILE_BYTES;
 #pragma unroll
-    for (int r = 0; r < 4; ++r) {
-      int key = min(t * BK + 16 * r + st_key, nkeys - 1);
+    for (int r = 0; r < 16 / NW; ++r) {
+      int key = min(t * BK + 4 * NW * r + st_key, nkeys - 1);
       const bf16_t* src = kbase + (long long)key * D + st_lc * 8;
-      char* dst = kb + (16 * r + 4 * wave) * ROW_BYTES;  // wave-uniform; lane lands at + 16 * lane
+      char* dst = kb + (4 * NW * r + 4 * wave) * ROW_BYTES;  // wave-uniform; lane lands at + 16 * lane
       __builtin_amdgcn_global_load_lds((const void __attribute__((address_space(1)))*)src,
                                        (void __attribute__((address_space(3)))*)dst, 16, 0, 0);
       if (OUT_V) {
@@ -270,90 +296,77 @@ __global__ void __launch_bounds__(256) __attribute__((amdgpu_waves_per_eu(1, 1))
     }
   };
 
-  // One pipeline step = one 32-key sub-tile n of the key range:
-  //   (a) start S^T of sub-tile n+1 (MFMA) and, meanwhile, find the row maxima of sub-tile n;
-  //   (b) if some row maximum outgrew its reference by more than 2^RESCALE_TH, move the
-  //       references and rescale that query tile's statistics and accumulators (rare);
-  //   (c) p = 2^t, running sums, bf16 P^T;  (d) O^T += X^T P^T.
-  // Steps alternate between two logit buffers, so nothing is copied.
-  auto logits = [&](const char* ktile, int st, f32x16 (&sacc)[2]) {
+  // Software pipeline over 32-key sub-tiles n = 0, 1, ...; step n, in issue order:
+  //   (a) if the row maxima seen in sub-tile n (found during step n-1) outgrew a reference by
+  //       more than 2^RESCALE_TH: move the references, rescale statistics and accumulators
+  //       (rare; the products of sub-tile n-1 are already in the accumulators);
+  //   (b) S^T of sub-tile n+1 (MFMA)   ||  (c) p = 2^t, running sums, bf16 P^T of sub-tile n;
+  //   (d) O^T += X^T P^T of sub-tile n (MFMA)  ||  (e) row maxima of sub-tile n+1.
+  // The decision of (a) is therefore known a whole step before it is branched on, and every
+  // MFMA group has independent vector work beside it.  Steps alternate between two logit
+  // buffers, so nothing is copied.
+  auto logits = [&](const char* ktile, int st, f32x16 (&sacc)[QT]) {
 #pragma unroll
-    for (int qt = 0; qt < 2; ++qt)
+    for (int qt = 0; qt < QT; ++qt)
 #pragma unroll
       for (int r = 0; r < 16; ++r) sacc[qt][r] = 0.f;
 #pragma unroll
     for (int ks = 0; ks < 8; ++ks) {
       bf16x8 a = lds_read_b128(ktile + st * 32 * ROW_BYTES + a_off[ks]);
 #pragma unroll
-      for (int qt = 0; qt < 2; ++qt)
+      for (int qt = 0; qt < QT; ++qt)
         sacc[qt] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(a, qreg[qt][ks], sacc[qt], 0, 0, 0);
     }
   };
-  static_assert(!(OUT_K && OUT_V), "one accumulator set per pass (see launch_r_update_flash)");
-  constexpr bool S_AHEAD = true;
-  auto step = [&](auto tail_c, auto next_c, f32x16 (&scur)[2], f32x16 (&snext)[2], const char* ktile, int st,
+  float mpend[QT];     // references that take effect at the start of the next step
+  bool moved = false;  // wave-uniform: some reference moves at the start of the next step
+  auto look_ahead = [&](f32x16 (&snext)[QT]) {
+    bool grow = false;
+#pragma unroll
+    for (int qt = 0; qt < QT; ++qt) {
+      const float cand = subtile_max(snext[qt]) * sc[qt];
+      grow = grow || (cand > msc[qt] + RESCALE_TH);
+      mpend[qt] = fmaxf(msc[qt], cand);
+    }
+    moved = __any(grow);
+  };
+  auto step = [&](auto tail_c, auto next_c, f32x16 (&scur)[QT], f32x16 (&snext)[QT], const char* ktile, int st,
                   const char* next_ktile, int next_st, int keys_left) {
     constexpr bool TAIL = decltype(tail_c)::value;
     constexpr bool HAS_NEXT = decltype(next_c)::value;
-    if (S_AHEAD) {
-      if (HAS_NEXT) logits(next_ktile, next_st, snext);
-    } else {
-      logits(ktile, st, scur);
-    }
-    float cand[2];
-    bool grow = false;
+    if (moved) {
 #pragma unroll
-    for (int qt = 0; qt < 2; ++qt) {
-      cand[qt] = subtile_max<TAIL>(scur[qt], g, keys_left) * sc[qt];
-      grow = grow || (cand[qt] > msc[qt] + RESCALE_TH);
-    }
-    if (__any(grow)) {
-      asm volatile("s_nop 15\n\ts_nop 15" ::: "memory");  // let in-flight MFMA results retire
-#pragma unroll
-      for (int qt = 0; qt < 2; ++qt) {
-        float mnew = fmaxf(msc[qt], cand[qt]);
-        float dl = msc[qt] - mnew;  // log2 of the rescale factor, <= 0
-        float alpha = __builtin_amdgcn_exp2f(dl);
+      for (int qt = 0; qt < QT; ++qt) {
+        const float dl = msc[qt] - mpend[qt];  // log2 of the rescale factor, <= 0
+        const float alpha = __builtin_amdgcn_exp2f(dl);
         if (ENT == 1) hsum[qt] = alpha * (hsum[qt] + dl * lsum[qt]);  // h <- a h + a log(a) l
         if (ENT != 0) lsum[qt] *= alpha;
         ltil[qt] *= alpha;
-        msc[qt] = mnew;
+        msc[qt] = mpend[qt];
 #pragma unroll
-        for (int ct = 0; ct < 4; ++ct) {
-          if (OUT_K) scale_acc(ok[qt][ct], alpha);
-          if (OUT_V) scale_acc(ov[qt][ct], alpha);
-        }
+        for (int ct = 0; ct < 4; ++ct) scale_acc(oacc[qt][ct], alpha);
       }
-      asm volatile("s_nop 7\n\ts_nop 7" ::: "memory");  // accumulator writes settle before the next MFMA
     }
-    bf16x8 pb[2][2];
+    if (HAS_NEXT) logits(next_ktile, next_st, snext);
+    bf16x8 pb[QT][2];
 #pragma unroll
-    for (int qt = 0; qt < 2; ++qt)
+    for (int qt = 0; qt < QT; ++qt)
       subtile_probs<ENT, TAIL>(scur[qt], sc[qt], msc[qt], ltil[qt], lsum[qt], hsum[qt], pb[qt], g, keys_left);
-    const char* vtile = ktile + TILE_BYTES;
+    const char* xtile = OUT_K ? ktile : ktile + TILE_BYTES;
 #pragma unroll
     for (int c = 0; c < 2; ++c) {
       const int koff = (st * 32 + c * 16) * ROW_BYTES;
 #pragma unroll
       for (int ct = 0; ct < 4; ++ct) {
-        if (OUT_K) {
-          bf16x4 lo = lds_read_tr(ktile + koff + t_off[ct][0]);
-          bf16x4 hi = lds_read_tr(ktile + koff + t_off[ct][1]);
-          bf16x8 a = __builtin_shufflevector(lo, hi, 0, 1, 2, 3, 4, 5, 6, 7);
+        bf16x4 lo = lds_read_tr(xtile + koff + t_off[ct][0]);
+        bf16x4 hi = lds_read_tr(xtile + koff + t_off[ct][1]);
+        bf16x8 a = __builtin_shufflevector(lo, hi, 0, 1, 2, 3, 4, 5, 6, 7);
 #pragma unroll
-          for (int qt = 0; qt < 2; ++qt)
-            ok[qt][ct] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(a, pb[qt][c], ok[qt][ct], 0, 0, 0);
-        }
-        if (OUT_V) {
-          bf16x4 lo = lds_read_tr(vtile + koff + t_off[ct][0]);
-          bf16x4 hi = lds_read_tr(vtile + koff + t_off[ct][1]);
-          bf16x8 a = __builtin_shufflevector(lo, hi, 0, 1, 2, 3, 4, 5, 6, 7);
-#pragma unroll
-          for (int qt = 0; qt < 2; ++qt)
-            ov[qt][ct] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(a, pb[qt][c], ov[qt][ct], 0, 0, 0);
-        }
+        for (int qt = 0; qt < QT; ++qt)
+          oacc[qt][ct] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(a, pb[qt][c], oacc[qt][ct], 0, 0, 0);
       }
     }
+    if (HAS_NEXT) look_ahead(snext);
   };
   using std::false_type;
   using std::true_type;
@@ -365,8 +378,9 @@ __global__ void __launch_bounds__(256) __attribute__((amdgpu_waves_per_eu(1, 1))
     if (ntiles > 1) issue_tile(1, 1);
     asm volatile("s_waitcnt vmcnt(0)" ::: "memory");
     __syncthreads();
-    f32x16 sA[2], sB[2];
-    if (S_AHEAD) logits(smem, 0, sA);
+    f32x16 sA[QT], sB[QT];
+    logits(smem, 0, sA);
+    look_ahead(sA);
     int buf = 0;  // buffer of tile t
     for (int t = 0; t < ntiles - 1; ++t) {
       if (t > 0) {
@@ -400,7 +414,7 @@ __global__ void __launch_bounds__(256) __attribute__((amdgpu_waves_per_eu(1, 1))
 
   // ---- epilogue ----------------------------------------------------------------------------
 #pragma unroll
-  for (int qt = 0; qt < 2; ++qt) {
+  for (int qt = 0; qt < QT; ++qt) {
     const float lt = ltil[qt] + __shfl_xor(ltil[qt], 32);
     const float inv = lt > 0.f ? 1.0f / lt : 0.f;
     const float l = ENT != 0 ? lsum[qt] + __shfl_xor(lsum[qt], 32) : lt;
@@ -421,10 +435,10 @@ __global__ void __launch_bounds__(256) __attribute__((amdgpu_waves_per_eu(1, 1))
 #pragma unroll
           for (int c = 0; c < 4; ++c) {
             uint2 w = *reinterpret_cast<const uint2*>(qp + 32 * ct + 8 * c + 4 * g);
-            dot += __uint_as_float(w.x << 16) * ok[qt][ct][4 * c + 0];
-            dot += __uint_as_float(w.x & 0xffff0000u) * ok[qt][ct][4 * c + 1];
-            dot += __uint_as_float(w.y << 16) * ok[qt][ct][4 * c + 2];
-            dot += __uint_as_float(w.y & 0xffff0000u) * ok[qt][ct][4 * c + 3];
+            dot += __uint_as_float(w.x << 16) * oacc[qt][ct][4 * c + 0];
+            dot += __uint_as_float(w.x & 0xffff0000u) * oacc[qt][ct][4 * c + 1];
+            dot += __uint_as_float(w.y << 16) * oacc[qt][ct][4 * c + 2];
+            dot += __uint_as_float(w.y & 0xffff0000u) * oacc[qt][ct][4 * c + 3];
           }
         dot += __shfl_xor(dot, 32);
         float mean_t = dot * inv * sc[qt];          // sum_l R_l (s_l sc), log2 units
@@ -439,14 +453,14 @@ __global__ void __launch_bounds__(256) __attribute__((amdgpu_waves_per_eu(1, 1))
             const int ch = 32 * ct + 8 * c + 4 * g;
             if (OUT_K) {
               uint2 w;
-              w.x = pack_bf16(ok[qt][ct][4 * c + 0] * inv, ok[qt][ct][4 * c + 1] * inv);
-              w.y = pack_bf16(ok[qt][ct][4 * c + 2] * inv, ok[qt][ct][4 * c + 3] * inv);
+              w.x = pack_bf16(oacc[qt][ct][4 * c + 0] * inv, oacc[qt][ct][4 * c + 1] * inv);
+              w.y = pack_bf16(oacc[qt][ct][4 * c + 2] * inv, oacc[qt][ct][4 * c + 3] * inv);
               *reinterpret_cast<uint2*>(P.outk + row * D + ch) = w;
             }
             if (OUT_V) {
               uint2 w;
-              w.x = pack_bf16(ov[qt][ct][4 * c + 0] * inv, ov[qt][ct][4 * c + 1] * inv);
-              w.y = pack_bf16(ov[qt][ct][4 * c + 2] * inv, ov[qt][ct][4 * c + 3] * inv);
+              w.x = pack_bf16(oacc[qt][ct][4 * c + 0] * inv, oacc[qt][ct][4 * c + 1] * inv);
+              w.y = pack_bf16(oacc[qt][ct][4 * c + 2] * inv, oacc[qt][ct][4 * c + 3] * inv);
               *reinterpret_cast<uint2*>(P.outv + row * D + ch) = w;
             }
           }
@@ -462,8 +476,8 @@ __global__ void __launch_bounds__(256) __attribute__((amdgpu_waves_per_eu(1, 1))
 #pragma unroll
           for (int c = 0; c < 4; ++c) {
             const int ch = 32 * ct + 8 * c + 4 * g;
-            float4 w = {ov[qt][ct][4 * c + 0] * inv, ov[qt][ct][4 * c + 1] * inv, ov[qt][ct][4 * c + 2] * inv,
-                        ov[qt][ct][4 * c + 3] * inv};
+            float4 w = {oacc[qt][ct][4 * c + 0] * inv, oacc[qt][ct][4 * c + 1] * inv, oacc[qt][ct][4 * c + 2] * inv,
+                        oacc[qt][ct][4 * c + 3] * inv};
             *reinterpret_cast<float4*>(P.part_o + prow * D + ch) = w;
           }
       }
@@ -502,7 +516,7 @@ hipError_t launch_flash(const FlashParams& P, hipStream_t st) {
     if (e != hipSuccess) return e;
     configured = true;
   }
-  hipLaunchKernelGGL(kern, dim3(P.blocks_per_xcd * 8), dim3(256), FLASH_LDS_BYTES, st, P);
+  hipLaunchKernelGGL(kern, dim3(P.blocks_per_xcd * 8), dim3(64 * NW), FLASH_LDS_BYTES, st, P);
   return hipGetLastError();
 }
 
