@@ -27,7 +27,7 @@ BF16_MFMA_PEAK_TFLOPS = 2500.0   # MI355X dense bf16 (published)
 HBM_PEAK_GBS = 8000.0            # MI355X HBM3E (published)
 
 
-def cpu_baseline(wl, q_bits, k_bits, v_bits, positions=48, rows=48):
+def cpu_baseline(wl, q_bits, k_bits, v_bits, positions=1024, rows=1024):
     """The oracle as it stands, on one head: `positions` query positions followed through
     the whole iteration (all T frames) plus `rows` first-frame rows recomputed exactly."""
     import numpy as np

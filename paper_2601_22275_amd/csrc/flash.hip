@@ -38,12 +38,19 @@ constexpr int BK = 64;          // key rows per LDS tile
 constexpr int QT = VM_FLASH_QT;
 constexpr int NW = VM_FLASH_NW;
 constexpr int BQ = 32 * QT * NW;  // query rows per workgroup
+constexpr int NSLOT = 4;          // LDS tile slots per tensor
 constexpr int ROW_BYTES = D * 2;
 constexpr int TILE_BYTES = BK * ROW_BYTES;  // 16 KB
 constexpr float LOG2E = 1.4426950408889634f;
 constexpr float LN2 = 0.6931471805599453f;
 constexpr float RESCALE_TH = 8.0f;  // rescale the accumulators only when a row max grows by 2^8
 constexpr float NEG_BIG = -1.0e30f;
+#ifndef VM_SCHED_GROUPS
+#define VM_SCHED_GROUPS 0
+#endif
+#ifndef VM_SCHED_VALU
+#define VM_SCHED_VALU 7
+#endif
 
 struct FlashParams {
   const bf16_t* q;      // query rows
@@ -91,36 +98,14 @@ __device__ __forceinline__ uint32_t pack_bf16(float a, float b) {
   return u;
 }
 
-// acc *= alpha for an MFMA accumulator tile that lives in accumulation registers.  VALU
-// instructions cannot address those, so each element takes the read / multiply / write
-// round trip explicitly; spelled as inline assembly so that the register allocator keeps the
-// tile in accumulation registers instead of migrating it to the (scarcer) vector registers.
-// The compiler does not see inside the statement, so the MFMA -> VALU read hazard (the
-// producing MFMA needs 16 passes plus 2 quad-cycles before its result may be read) and the
-// VALU write -> MFMA read hazard are covered by s_nop inside the same statement: the
-// statement is ordered after the producing MFMA and before the consuming one by its operands.
+// acc *= alpha for an MFMA accumulator tile.  This file is compiled with the MFMA results
+// in ordinary vector registers (-mllvm -amdgpu-mfma-vgpr-form=1): with two waves per SIMD
+// a wave owns 256 registers in total, the accumulators need only 64 of them, and keeping
+// everything in one register class lets plain VALU code rescale them and spares the
+// accumulation-register round trips.
 __device__ __forceinline__ void scale_acc(f32x16& acc, float alpha) {
 #pragma unroll
-  for (int h8 = 0; h8 < 2; ++h8) {
-    float x0 = acc[8 * h8 + 0], x1 = acc[8 * h8 + 1], x2 = acc[8 * h8 + 2], x3 = acc[8 * h8 + 3];
-    float x4 = acc[8 * h8 + 4], x5 = acc[8 * h8 + 5], x6 = acc[8 * h8 + 6], x7 = acc[8 * h8 + 7];
-    float tmp;
-    asm volatile(
-        "s_nop 15\n\ts_nop 3\n\t"
-        "v_accvgpr_read_b32 %8, %0\n\tv_mul_f32 %8, %8, %9\n\tv_accvgpr_write_b32 %0, %8\n\t"
-        "v_accvgpr_read_b32 %8, %1\n\tv_mul_f32 %8, %8, %9\n\tv_accvgpr_write_b32 %1, %8\n\t"
-        "v_accvgpr_read_b32 %8, %2\n\tv_mul_f32 %8, %8, %9\n\tv_accvgpr_write_b32 %2, %8\n\t"
-        "v_accvgpr_read_b32 %8, %3\n\tv_mul_f32 %8, %8, %9\n\tv_accvgpr_write_b32 %3, %8\n\t"
-        "v_accvgpr_read_b32 %8, %4\n\tv_mul_f32 %8, %8, %9\n\tv_accvgpr_write_b32 %4, %8\n\t"
-        "v_accvgpr_read_b32 %8, %5\n\tv_mul_f32 %8, %8, %9\n\tv_accvgpr_write_b32 %5, %8\n\t"
-        "v_accvgpr_read_b32 %8, %6\n\tv_mul_f32 %8, %8, %9\n\tv_accvgpr_write_b32 %6, %8\n\t"
-        "v_accvgpr_read_b32 %8, %7\n\tv_mul_f32 %8, %8, %9\n\tv_accvgpr_write_b32 %7, %8\n\t"
-        "s_nop 3"
-        : "+a"(x0), "+a"(x1), "+a"(x2), "+a"(x3), "+a"(x4), "+a"(x5), "+a"(x6), "+a"(x7), "=&v"(tmp)
-        : "v"(alpha));
-    acc[8 * h8 + 0] = x0; acc[8 * h8 + 1] = x1; acc[8 * h8 + 2] = x2; acc[8 * h8 + 3] = x3;
-    acc[8 * h8 + 4] = x4; acc[8 * h8 + 5] = x5; acc[8 * h8 + 6] = x6; acc[8 * h8 + 7] = x7;
-  }
+  for (int r = 0; r < 16; ++r) acc[r] *= alpha;
 }
 
 // Row maximum of one 32-key sub-tile for one 32-query tile.  `s` holds the raw logits
@@ -185,7 +170,7 @@ __device__ __forceinline__ void subtile_probs(const f32x16& s, float sc, float m
 
 template <bool OUT_K, bool OUT_V, int ENT, bool SPLIT>
 __global__ void __launch_bounds__(64 * NW) flash_kernel(FlashParams P) {
-  extern __shared__ __attribute__((aligned(16))) char smem[];  // [3 buffers][K|V][64 rows][256 B]
+  extern __shared__ __attribute__((aligned(16))) char smem[];  // [K|V][NSLOT][64 rows][256 B]
 
   // XCD-aware placement: hardware deals workgroups to the 8 XCDs round-robin, so give each
   // XCD one contiguous range of work items; the query blocks of one (head, frame) then share
@@ -279,8 +264,9 @@ __global__ void __launch_bounds__(64 * NW) flash_kernel(FlashParams P) {
   }
 
   // ---- tile staging ----------------------------------------------------------------------
-  auto issue_tile = [&](int t, int buf) {
-    char* kb = smem + buf * 2 * TILE_BYTES;
+  // LDS: NSLOT K tiles at [0, NSLOT * 16 KB), then NSLOT V tiles; tile t lives in slot t & 3.
+  auto issue_tile = [&](int t) {
+    char* kb = smem + (t & (NSLOT - 1)) * TILE_BYTES;
 #pragma unroll
     for (int r = 0; r < 16 / NW; ++r) {
       int key = min(t * BK + 4 * NW * r + st_key, nkeys - 1);
@@ -291,20 +277,20 @@ __global__ void __launch_bounds__(64 * NW) flash_kernel(FlashParams P) {
       if (OUT_V) {
         const bf16_t* vsrc = vbase + (long long)key * D + st_lc * 8;
         __builtin_amdgcn_global_load_lds((const void __attribute__((address_space(1)))*)vsrc,
-                                         (void __attribute__((address_space(3)))*)(dst + TILE_BYTES), 16, 0, 0);
+                                         (void __attribute__((address_space(3)))*)(dst + NSLOT * TILE_BYTES), 16, 0, 0);
       }
     }
   };
 
-  // Software pipeline over 32-key sub-tiles n = 0, 1, ...; step n, in issue order:
-  //   (a) if the row maxima seen in sub-tile n (found during step n-1) outgrew a reference by
-  //       more than 2^RESCALE_TH: move the references, rescale statistics and accumulators
-  //       (rare; the products of sub-tile n-1 are already in the accumulators);
-  //   (b) S^T of sub-tile n+1 (MFMA)   ||  (c) p = 2^t, running sums, bf16 P^T of sub-tile n;
-  //   (d) O^T += X^T P^T of sub-tile n (MFMA)  ||  (e) row maxima of sub-tile n+1.
-  // The decision of (a) is therefore known a whole step before it is branched on, and every
-  // MFMA group has independent vector work beside it.  Steps alternate between two logit
-  // buffers, so nothing is copied.
+  // Software pipeline over 32-key sub-tiles n = 0, 1, ...  Step n carries two independent
+  // instruction streams:
+  //   matrix:  S^T of sub-tile n+1, then O^T += X^T P^T of sub-tile n-1 (P^T from step n-1);
+  //   vector:  p = 2^t, running sums and bf16 P^T of sub-tile n, then the row maxima of
+  //            sub-tile n+1 (which decide whether the references move at step n+1).
+  // A reference move (rare: only when a row maximum outgrew its reference by 2^RESCALE_TH)
+  // rescales the scalar statistics at the top of the step, before they are added to, and the
+  // accumulators at the bottom, after the products of sub-tile n-1 (computed against the old
+  // reference) have been issued and before those of sub-tile n are.
   auto logits = [&](const char* ktile, int st, f32x16 (&sacc)[QT]) {
 #pragma unroll
     for (int qt = 0; qt < QT; ++qt)
@@ -318,41 +304,9 @@ __global__ void __launch_bounds__(64 * NW) flash_kernel(FlashParams P) {
         sacc[qt] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(a, qreg[qt][ks], sacc[qt], 0, 0, 0);
     }
   };
-  float mpend[QT];     // references that take effect at the start of the next step
-  bool moved = false;  // wave-uniform: some reference moves at the start of the next step
-  auto look_ahead = [&](f32x16 (&snext)[QT]) {
-    bool grow = false;
-#pragma unroll
-    for (int qt = 0; qt < QT; ++qt) {
-      const float cand = subtile_max(snext[qt]) * sc[qt];
-      grow = grow || (cand > msc[qt] + RESCALE_TH);
-      mpend[qt] = fmaxf(msc[qt], cand);
-    }
-    moved = __any(grow);
-  };
-  auto step = [&](auto tail_c, auto next_c, f32x16 (&scur)[QT], f32x16 (&snext)[QT], const char* ktile, int st,
-                  const char* next_ktile, int next_st, int keys_left) {
-    constexpr bool TAIL = decltype(tail_c)::value;
-    constexpr bool HAS_NEXT = decltype(next_c)::value;
-    if (moved) {
-#pragma unroll
-      for (int qt = 0; qt < QT; ++qt) {
-        const float dl = msc[qt] - mpend[qt];  // log2 of the rescale factor, <= 0
-        const float alpha = __builtin_amdgcn_exp2f(dl);
-        if (ENT == 1) hsum[qt] = alpha * (hsum[qt] + dl * lsum[qt]);  // h <- a h + a log(a) l
-        if (ENT != 0) lsum[qt] *= alpha;
-        ltil[qt] *= alpha;
-        msc[qt] = mpend[qt];
-#pragma unroll
-        for (int ct = 0; ct < 4; ++ct) scale_acc(oacc[qt][ct], alpha);
-      }
-    }
-    if (HAS_NEXT) logits(next_ktile, next_st, snext);
-    bf16x8 pb[QT][2];
-#pragma unroll
-    for (int qt = 0; qt < QT; ++qt)
-      subtile_probs<ENT, TAIL>(scur[qt], sc[qt], msc[qt], ltil[qt], lsum[qt], hsum[qt], pb[qt], g, keys_left);
-    const char* xtile = OUT_K ? ktile : ktile + TILE_BYTES;
+  // O^T += X^T P^T for sub-tile `st` of the tile whose K slot is `ktile`
+  auto accumulate = [&](const char* ktile, int st, bf16x8 (&pb)[QT][2]) {
+    const char* xtile = OUT_K ? ktile : ktile + NSLOT * TILE_BYTES;
 #pragma unroll
     for (int c = 0; c < 2; ++c) {
       const int koff = (st * 32 + c * 16) * ROW_BYTES;
@@ -366,49 +320,117 @@ __global__ void __launch_bounds__(64 * NW) flash_kernel(FlashParams P) {
           oacc[qt][ct] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(a, pb[qt][c], oacc[qt][ct], 0, 0, 0);
       }
     }
+  };
+  float mpend[QT];     // references that take effect at the start of the next step
+  bool moved = false;  // wave-uniform: some reference moves at the start of the next step
+  auto look_ahead = [&](f32x16 (&snext)[QT]) {
+    bool grow = false;
+    float cand[QT];
+#pragma unroll
+    for (int qt = 0; qt < QT; ++qt) {
+      cand[qt] = subtile_max(snext[qt]) * sc[qt];
+      grow = grow || (cand[qt] > msc[qt] + RESCALE_TH);
+    }
+    moved = __any(grow);
+#pragma unroll
+    for (int qt = 0; qt < QT; ++qt) mpend[qt] = moved ? fmaxf(msc[qt], cand[qt]) : msc[qt];
+  };
+  auto step = [&](auto tail_c, auto next_c, f32x16 (&scur)[QT], f32x16 (&snext)[QT], bf16x8 (&pbprev)[QT][2],
+                  bf16x8 (&pbcur)[QT][2], const char* next_ktile, int next_st, const char* prev_ktile, int prev_st,
+                  int keys_left) {
+    constexpr bool TAIL = decltype(tail_c)::value;
+    constexpr bool HAS_NEXT = decltype(next_c)::value;
+    const bool moved_now = moved;
+    float alpha[QT];
+#pragma unroll
+    for (int qt = 0; qt < QT; ++qt) {
+      const float dl = msc[qt] - mpend[qt];  // log2 of the rescale factor: <= 0, and 0 when nothing moved
+      alpha[qt] = __builtin_amdgcn_exp2f(dl);
+      if (ENT == 1) hsum[qt] = alpha[qt] * (hsum[qt] + dl * lsum[qt]);  // h <- a h + a log(a) l
+      if (ENT != 0) lsum[qt] *= alpha[qt];
+      ltil[qt] *= alpha[qt];
+      msc[qt] = mpend[qt];
+    }
+    if (HAS_NEXT) logits(next_ktile, next_st, snext);
+    accumulate(prev_ktile, prev_st, pbprev);
+#pragma unroll
+    for (int qt = 0; qt < QT; ++qt)
+      subtile_probs<ENT, TAIL>(scur[qt], sc[qt], msc[qt], ltil[qt], lsum[qt], hsum[qt], pbcur[qt], g, keys_left);
     if (HAS_NEXT) look_ahead(snext);
+#if VM_SCHED_GROUPS
+    // Issue order handed to the scheduler: the LDS reads of the first MFMA group up front, then
+    // one MFMA at a time with the LDS reads of a later MFMA and a slice of the vector work.
+    __builtin_amdgcn_sched_group_barrier(0x100, HAS_NEXT ? 8 : 0, 0);
+#pragma unroll
+    for (int i = 0; i < (HAS_NEXT ? 8 * QT : 0); ++i) {
+      __builtin_amdgcn_sched_group_barrier(0x008, 1, 0);
+      __builtin_amdgcn_sched_group_barrier(0x100, 2 / QT > 0 ? 2 / QT : 1, 0);
+      __builtin_amdgcn_sched_group_barrier(0x002, VM_SCHED_VALU, 0);
+    }
+#pragma unroll
+    for (int i = 0; i < 8 * QT; ++i) {
+      __builtin_amdgcn_sched_group_barrier(0x008, 1, 0);
+      __builtin_amdgcn_sched_group_barrier(0x002, VM_SCHED_VALU, 0);
+    }
+#endif
+    if (moved_now) {
+#pragma unroll
+      for (int qt = 0; qt < QT; ++qt)
+#pragma unroll
+        for (int ct = 0; ct < 4; ++ct) scale_acc(oacc[qt][ct], alpha[qt]);
+    }
   };
   using std::false_type;
   using std::true_type;
 
   if (ntiles > 0) {
-    // Three LDS buffers: while tile t is consumed, tile t+1 is resident (its first sub-tile
-    // is needed one step ahead) and tile t+2 is in flight.
-    issue_tile(0, 0);
-    if (ntiles > 1) issue_tile(1, 1);
+    // Four LDS slots, tile t in slot t & 3: during tile t the products of the last sub-tile of
+    // tile t-1 are still outstanding, tile t+1 is resident (its first sub-tile is needed one
+    // step ahead) and tile t+2 is in flight.
+    issue_tile(0);
+    if (ntiles > 1) issue_tile(1);
     asm volatile("s_waitcnt vmcnt(0)" ::: "memory");
     __syncthreads();
     f32x16 sA[QT], sB[QT];
+    bf16x8 pbA[QT][2], pbB[QT][2];
+    {
+      const bf16x8 zero = {0, 0, 0, 0, 0, 0, 0, 0};
+#pragma unroll
+      for (int qt = 0; qt < QT; ++qt)
+#pragma unroll
+        for (int c = 0; c < 2; ++c) pbB[qt][c] = zero;  // step 0 has no predecessor: it adds P^T = 0
+    }
     logits(smem, 0, sA);
     look_ahead(sA);
-    int buf = 0;  // buffer of tile t
     for (int t = 0; t < ntiles - 1; ++t) {
       if (t > 0) {
         asm volatile("s_waitcnt vmcnt(0)" ::: "memory");
-        __syncthreads();  // tile t+1 has landed for everyone; everyone is done with tile t-1
+        __syncthreads();  // tile t+1 has landed for everyone; everyone is done with tile t-2
       }
-      const int nbuf = buf == 2 ? 0 : buf + 1;
-      if (t + 2 < ntiles) issue_tile(t + 2, nbuf == 2 ? 0 : nbuf + 1);
-      const char* kt = smem + buf * 2 * TILE_BYTES;
-      const char* kn = smem + nbuf * 2 * TILE_BYTES;
-      step(false_type{}, true_type{}, sA, sB, kt, 0, kt, 1, 32);
-      step(false_type{}, true_type{}, sB, sA, kt, 1, kn, 0, 32);
-      buf = nbuf;
+      if (t + 2 < ntiles) issue_tile(t + 2);
+      const char* kp = smem + ((t + 3) & 3) * TILE_BYTES;  // tile t-1
+      const char* kt = smem + (t & 3) * TILE_BYTES;
+      const char* kn = smem + ((t + 1) & 3) * TILE_BYTES;
+      step(false_type{}, true_type{}, sA, sB, pbB, pbA, kt, 1, t > 0 ? kp : kt, 1, 32);
+      step(false_type{}, true_type{}, sB, sA, pbA, pbB, kn, 0, kt, 0, 32);
     }
     {
-      if (ntiles > 1) {
+      const int t = ntiles - 1;
+      if (t > 0) {
         asm volatile("s_waitcnt vmcnt(0)" ::: "memory");
         __syncthreads();
       }
-      const char* kt = smem + buf * 2 * TILE_BYTES;
-      const int left = nkeys - (ntiles - 1) * BK;  // 1..64 keys in the last tile
+      const char* kp = smem + ((t + 3) & 3) * TILE_BYTES;
+      const char* kt = smem + (t & 3) * TILE_BYTES;
+      const int left = nkeys - t * BK;  // 1..64 keys in the last tile
       if (left == BK) {
-        step(false_type{}, true_type{}, sA, sB, kt, 0, kt, 1, 32);
-        step(false_type{}, false_type{}, sB, sA, kt, 1, kt, 0, 32);
+        step(false_type{}, true_type{}, sA, sB, pbB, pbA, kt, 1, t > 0 ? kp : kt, 1, 32);
+        step(false_type{}, false_type{}, sB, sA, pbA, pbB, kt, 0, kt, 0, 32);
       } else {
-        step(true_type{}, true_type{}, sA, sB, kt, 0, kt, 1, left);
-        step(true_type{}, false_type{}, sB, sA, kt, 1, kt, 0, left - 32);
+        step(true_type{}, true_type{}, sA, sB, pbB, pbA, kt, 1, t > 0 ? kp : kt, 1, left);
+        step(true_type{}, false_type{}, sB, sA, pbA, pbB, kt, 0, kt, 0, left - 32);
       }
+      accumulate(kt, 1, pbB);  // drain: the products of the last sub-tile
     }
   }
 
@@ -505,7 +527,7 @@ __global__ void __launch_bounds__(128) merge_splits_kernel(const float* __restri
   out[(prob * out_rows_per_problem + row) * D + c] = f32_to_bf16(acc / wsum);
 }
 
-constexpr int FLASH_LDS_BYTES = 3 * 2 * TILE_BYTES;  // 96 KB
+constexpr int FLASH_LDS_BYTES = 2 * NSLOT * TILE_BYTES;  // four K slots + four V slots = 128 KB
 
 template <bool OUT_K, bool OUT_V, int ENT, bool SPLIT>
 hipError_t launch_flash(const FlashParams& P, hipStream_t st) {
