@@ -27,25 +27,30 @@ BF16_MFMA_PEAK_TFLOPS = 2500.0   # MI355X dense bf16 (published)
 HBM_PEAK_GBS = 8000.0            # MI355X HBM3E (published)
 
 
-def cpu_baseline(wl, q_bits, k_bits, v_bits, positions=1024, rows=1024):
-    """The oracle as it stands, on one head: `positions` query positions followed through
-    the whole iteration (all T frames) plus `rows` first-frame rows recomputed exactly."""
+def cpu_baseline(wl, q_bits, k_bits, v_bits, positions=1024, rows=1024, min_seconds=12.0, max_heads=8):
+    """The oracle as it stands: per head, `positions` query positions followed through the
+    whole iteration (all T frames) plus `rows` first-frame rows recomputed exactly; heads are
+    added until about `min_seconds` of CPU work have been timed."""
     import numpy as np
     from oracle import vmonarch_oracle as O
 
-    q, k, v = (O.widen_bf16(x) for x in (q_bits, k_bits, v_bits))
     rng = np.random.default_rng(5)
     pos = np.sort(rng.choice(wl.b, size=min(positions, wl.b), replace=False))
-    t0 = time.perf_counter()
-    O.monarch_attention(q, k, v, wl.T, wl.b, wl.iters, recompute=False, positions=pos)
-    if wl.recompute:
-        O.first_frame_attention(q, k, v, wl.b, rows=pos[:rows])
-    dt = time.perf_counter() - t0
     T, b, d, N = wl.T, wl.b, wl.d, wl.N
     s = len(pos)
-    flops = s * ((wl.iters - 1) * 4 * T * b * d + 6 * T * b * d + wl.iters * 4 * T * T * d)
+    per_head = s * ((wl.iters - 1) * 4 * T * b * d + 6 * T * b * d + wl.iters * 4 * T * T * d)
     if wl.recompute:
-        flops += min(rows, s) * 4 * N * d
+        per_head += min(rows, s) * 4 * N * d
+    dt, flops, nheads = 0.0, 0.0, 0
+    while dt < min_seconds and nheads < min(max_heads, len(q_bits)):
+        q, k, v = (O.widen_bf16(x[nheads]) for x in (q_bits, k_bits, v_bits))
+        t0 = time.perf_counter()
+        O.monarch_attention(q, k, v, wl.T, wl.b, wl.iters, recompute=False, positions=pos)
+        if wl.recompute:
+            O.first_frame_attention(q, k, v, wl.b, rows=pos[:rows])
+        dt += time.perf_counter() - t0
+        flops += per_head
+        nheads += 1
     try:
         cores = len(os.sched_getaffinity(0))
     except AttributeError:  # pragma: no cover
@@ -55,11 +60,24 @@ def cpu_baseline(wl, q_bits, k_bits, v_bits, positions=1024, rows=1024):
         cores = min(cores, int(omp))
     return {
         "value": flops / dt / 1e12, "unit": "TFLOP/s", "cores": cores, "kind": "oracle",
-        "sample": f"1 head, {s} of {b} query positions x all {T} frames through {wl.iters} sweeps"
+        "sample": f"{nheads} head(s), {s} of {b} query positions x all {T} frames through {wl.iters} sweeps"
                   + (f" + {min(rows, s)} first-frame rows over all {N} keys" if wl.recompute else "")
                   + f", fp64 NumPy, {dt:.1f} s",
         "seconds": dt,
     }
+
+
+def recorded_traffic():
+    """HBM bytes per launch of the dominant kernel from the committed rocprofv3 --pmc summary
+    (FETCH_SIZE and WRITE_SIZE runs scaled by a copy of known size), or None."""
+    path = os.path.join(ROOT, "profiles", "attention_long-81x28x52_hbm_traffic.txt")
+    try:
+        for line in open(path):
+            if line.startswith("dominant_kernel_hbm_bytes_per_launch:"):
+                return float(line.split(":", 1)[1])
+    except OSError:
+        pass
+    return None
 
 
 def main() -> int:
@@ -70,6 +88,8 @@ def main() -> int:
     ap.add_argument("--workload", default="long-81x28x52")
     ap.add_argument("--entropy", choices=["online", "identity"], default="online")
     ap.add_argument("--no-cpu-baseline", action="store_true")
+    ap.add_argument("--copy-calibration", action="store_true",
+                    help="also run one token-permutation copy of known size (reference for HBM byte counters)")
     args = ap.parse_args()
     if args.gpus != 1:
         print("bench.py: this build runs on ONE GPU only (no sharding, no collectives); use --gpus 1", file=sys.stderr)
@@ -150,7 +170,9 @@ def main() -> int:
             fl, t_ms, what = 6.0 * BH * T * b * b * d, phases["r_update_last"], "R-update of the last sweep (two launches: R K pass and R V pass)"
         ach = fl / (t_ms * 1e-3) / 1e12
         roofline = {"bound": "mfma", "achieved": ach, "peak": BF16_MFMA_PEAK_TFLOPS, "unit": "TFLOP/s",
-                    "frac": ach / BF16_MFMA_PEAK_TFLOPS, "traffic": None, "kernel": what,
+                    "frac": ach / BF16_MFMA_PEAK_TFLOPS,
+                    "traffic": recorded_traffic() if wl.name == "long-81x28x52" and "r_update" in phases else None,
+                    "kernel": what,
                     "flops_per_launch": fl, "ms_per_launch": t_ms}
     if "l_update" in phases:
         # fitting L-update: reads q and alpha_L, writes alpha_R (3 token tensors) + c_L, c_R
@@ -160,9 +182,14 @@ def main() -> int:
                      "peak": HBM_PEAK_GBS, "unit": "GB/s",
                      "frac": by / (phases["l_update"] * 1e-3) / 1e9 / HBM_PEAK_GBS}
 
+    if args.copy_calibration:
+        # reads and writes B*heads*N*d*elem bytes each: the yardstick for FETCH_SIZE / WRITE_SIZE
+        binding.permute_tokens(tq, wl.T, wl.Hs, wl.Ws, True)
+        torch.cuda.synchronize()
+
     cpu = None
     if not args.no_cpu_baseline and bf16:
-        cpu = cpu_baseline(wl, q[0], k[0], v[0])
+        cpu = cpu_baseline(wl, q, k, v)
 
     rec = {
         "metric": "spatio-temporal Monarch attention, effective TFLOP/s (algorithmic FLOPs / time per call)",
