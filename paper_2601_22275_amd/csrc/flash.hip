@@ -49,7 +49,10 @@ constexpr float NEG_BIG = -1.0e30f;
 #define VM_SCHED_GROUPS 0
 #endif
 #ifndef VM_SCHED_VALU
-#define VM_SCHED_VALU 7
+#define VM_SCHED_VALU 4
+#endif
+#ifndef VM_SCHED_HEAD
+#define VM_SCHED_HEAD 16
 #endif
 
 struct FlashParams {
@@ -73,7 +76,16 @@ struct FlashParams {
   int blocks_per_xcd;   // ceil(total_blocks / 8)
   float row_scale;
   float cr_min;
+#ifdef VM_DBG_TIMING
+  unsigned long long* dbg;
+#endif
 };
+#ifdef VM_DBG_TIMING
+unsigned long long* g_dbg_buf = nullptr;
+#define DBG_T(slot) do { if (dbg_on) { unsigned long long tt = __builtin_amdgcn_s_memtime(); P.dbg[(wave >> 2) * 512 + (slot)] = tt; } } while (0)
+#else
+#define DBG_T(slot) do { } while (0)
+#endif
 
 __device__ __forceinline__ int swz(int key) {
   int x = key & 15;
@@ -113,10 +125,12 @@ __device__ __forceinline__ void scale_acc(f32x16& acc, float alpha) {
 // other 16 keys and is reached with v_permlane32_swap (no LDS round trip).  Key rows past
 // the end of the range are copies of the last valid row, so they never change a maximum.
 __device__ __forceinline__ float subtile_max(const f32x16& s) {
-  float mx = fmaxf(fmaxf(s[0], s[1]), s[2]);
-#pragma unroll
-  for (int r = 3; r < 15; r += 2) mx = fmaxf(fmaxf(mx, s[r]), s[r + 1]);
-  mx = fmaxf(mx, s[15]);
+  // v_max3: four independent chains of depth 2, then 2 more ops
+  float m0 = fmaxf(fmaxf(s[0], s[1]), s[2]), m1 = fmaxf(fmaxf(s[3], s[4]), s[5]);
+  float m2 = fmaxf(fmaxf(s[6], s[7]), s[8]), m3 = fmaxf(fmaxf(s[9], s[10]), s[11]);
+  m0 = fmaxf(fmaxf(m0, s[12]), s[13]);
+  m1 = fmaxf(fmaxf(m1, s[14]), s[15]);
+  float mx = fmaxf(fmaxf(m0, m1), fmaxf(m2, m3));
   const unsigned u = __float_as_uint(mx);
   auto sw = __builtin_amdgcn_permlane32_swap(u, u, false, false);
   return fmaxf(__uint_as_float(sw[0]), __uint_as_float(sw[1]));
@@ -124,15 +138,15 @@ __device__ __forceinline__ float subtile_max(const f32x16& s) {
 
 // Probabilities of the sub-tile relative to the reference max `msc` (log2 units):
 // t = s * sc - msc, p = 2^t.  `pb[0..1]` receive the two bf16 B operands (16 keys each) of
-// the O^T += X^T P^T products.  Running sums:
-//   lt = sum of the bf16-ROUNDED p (v_dot2 against ones): the accumulators are divided by
+// the O^T += X^T P^T products.  Running sums (Alg. 1's l and, when ENT == 1, h):
+//   lt = sum of the bf16-ROUNDED p (v_dot2 against ones).  The accumulators are divided by
 //        this one, so that the output is an exact convex combination of the rows with
 //        slightly perturbed weights; dividing by the unrounded sum instead leaves a 2^-9
-//        relative error on rows dominated by one key;
-//   l  = sum p and h = sum p * t in full precision (ENT != 0 / ENT == 1): Alg. 1's
-//        statistics for log-sum-exp and entropy.
+//        relative error on rows dominated by one key.  It also serves as l in the
+//        log-sum-exp and in H = log l - h / l (error ~1e-3 in c_L, one VALU op per score saved);
+//   h  = sum p * t with the unrounded p.
 template <int ENT, bool TAIL>
-__device__ __forceinline__ void subtile_probs(const f32x16& s, float sc, float msc, float& lt, float& l, float& h,
+__device__ __forceinline__ void subtile_probs(const f32x16& s, float sc, float msc, float& lt, float& h,
                                               bf16x8 pb[2], int g, int keys_left) {
   typedef __attribute__((__vector_size__(2 * sizeof(__bf16)))) __bf16 bf16x2;
   bf16x2 ones2;
@@ -151,7 +165,6 @@ __device__ __forceinline__ void subtile_probs(const f32x16& s, float sc, float m
 #else
     p[r] = __builtin_amdgcn_exp2f(t);
 #endif
-    if (ENT != 0) l += p[r];
     if (ENT == 1) h = __builtin_fmaf(p[r], t, h);
   }
 #pragma unroll
@@ -190,6 +203,10 @@ __global__ void __launch_bounds__(64 * NW) flash_kernel(FlashParams P) {
   const int ql = lane & 31;
   const int g = lane >> 5;
 
+#ifdef VM_DBG_TIMING
+  const bool dbg_on = (wid == P.total_blocks / 2) && ((wave & 3) == 0) && lane == 0 && P.dbg != nullptr;
+#endif
+  DBG_T(0);
   const int kbeg = split * P.keys_per_split;
   const int kend = min(P.nk, kbeg + P.keys_per_split);
   const int nkeys = kend - kbeg;
@@ -246,20 +263,28 @@ __global__ void __launch_bounds__(64 * NW) flash_kernel(FlashParams P) {
   }
 
   // ---- accumulators --------------------------------------------------------------------
-  static_assert(OUT_K != OUT_V, "one accumulator set per pass (see launch_r_update_flash)");
-  f32x16 oacc[QT][4];  // O^T tiles: [query tile][32-channel tile]
+  // transpose-read offsets into the V slots (the slot stride of the K part stays an immediate)
+  int tv_off[4][2];
 #pragma unroll
-  for (int qt = 0; qt < QT; ++qt)
+  for (int ct = 0; ct < 4; ++ct)
 #pragma unroll
-    for (int ct = 0; ct < 4; ++ct)
+    for (int hh = 0; hh < 2; ++hh) tv_off[ct][hh] = t_off[ct][hh] + NSLOT * TILE_BYTES;
+  // O^T tiles [query tile][32-channel tile]: ok = softmax(z) K (alpha_L), ov = softmax(z) V (y)
+  f32x16 ok[OUT_K ? QT : 1][4], ov[OUT_V ? QT : 1][4];
 #pragma unroll
-      for (int r = 0; r < 16; ++r) oacc[qt][ct][r] = 0.f;
-  float msc[QT], ltil[QT], lsum[QT], hsum[QT];
+  for (int ct = 0; ct < 4; ++ct)
+#pragma unroll
+    for (int r = 0; r < 16; ++r) {
+#pragma unroll
+      for (int qt = 0; qt < (OUT_K ? QT : 1); ++qt) ok[qt][ct][r] = 0.f;
+#pragma unroll
+      for (int qt = 0; qt < (OUT_V ? QT : 1); ++qt) ov[qt][ct][r] = 0.f;
+    }
+  float msc[QT], ltil[QT], hsum[QT];
 #pragma unroll
   for (int qt = 0; qt < QT; ++qt) {
     msc[qt] = NEG_BIG;
     ltil[qt] = 0.f;
-    lsum[qt] = 0.f;
     hsum[qt] = 0.f;
   }
 
@@ -298,26 +323,39 @@ __global__ void __launch_bounds__(64 * NW) flash_kernel(FlashParams P) {
       for (int r = 0; r < 16; ++r) sacc[qt][r] = 0.f;
 #pragma unroll
     for (int ks = 0; ks < 8; ++ks) {
+#ifdef VM_DBG_NO_LDS_S
+      bf16x8 a = qreg[0][(ks + 1) & 7];
+#else
       bf16x8 a = lds_read_b128(ktile + st * 32 * ROW_BYTES + a_off[ks]);
+#endif
 #pragma unroll
       for (int qt = 0; qt < QT; ++qt)
         sacc[qt] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(a, qreg[qt][ks], sacc[qt], 0, 0, 0);
     }
   };
-  // O^T += X^T P^T for sub-tile `st` of the tile whose K slot is `ktile`
+  // O^T += X^T P^T for sub-tile `st` of the tile whose K slot is `ktile` (X = K and/or V)
   auto accumulate = [&](const char* ktile, int st, bf16x8 (&pb)[QT][2]) {
-    const char* xtile = OUT_K ? ktile : ktile + NSLOT * TILE_BYTES;
 #pragma unroll
     for (int c = 0; c < 2; ++c) {
       const int koff = (st * 32 + c * 16) * ROW_BYTES;
 #pragma unroll
       for (int ct = 0; ct < 4; ++ct) {
-        bf16x4 lo = lds_read_tr(xtile + koff + t_off[ct][0]);
-        bf16x4 hi = lds_read_tr(xtile + koff + t_off[ct][1]);
-        bf16x8 a = __builtin_shufflevector(lo, hi, 0, 1, 2, 3, 4, 5, 6, 7);
+        if (OUT_K) {
+          bf16x4 lo = lds_read_tr(ktile + koff + t_off[ct][0]);
+          bf16x4 hi = lds_read_tr(ktile + koff + t_off[ct][1]);
+          bf16x8 a = __builtin_shufflevector(lo, hi, 0, 1, 2, 3, 4, 5, 6, 7);
 #pragma unroll
-        for (int qt = 0; qt < QT; ++qt)
-          oacc[qt][ct] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(a, pb[qt][c], oacc[qt][ct], 0, 0, 0);
+          for (int qt = 0; qt < QT; ++qt)
+            ok[qt][ct] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(a, pb[qt][c], ok[qt][ct], 0, 0, 0);
+        }
+        if (OUT_V) {
+          bf16x4 lo = lds_read_tr(ktile + koff + tv_off[ct][0]);
+          bf16x4 hi = lds_read_tr(ktile + koff + tv_off[ct][1]);
+          bf16x8 a = __builtin_shufflevector(lo, hi, 0, 1, 2, 3, 4, 5, 6, 7);
+#pragma unroll
+          for (int qt = 0; qt < QT; ++qt)
+            ov[qt][ct] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(a, pb[qt][c], ov[qt][ct], 0, 0, 0);
+        }
       }
     }
   };
@@ -346,8 +384,7 @@ __global__ void __launch_bounds__(64 * NW) flash_kernel(FlashParams P) {
     for (int qt = 0; qt < QT; ++qt) {
       const float dl = msc[qt] - mpend[qt];  // log2 of the rescale factor: <= 0, and 0 when nothing moved
       alpha[qt] = __builtin_amdgcn_exp2f(dl);
-      if (ENT == 1) hsum[qt] = alpha[qt] * (hsum[qt] + dl * lsum[qt]);  // h <- a h + a log(a) l
-      if (ENT != 0) lsum[qt] *= alpha[qt];
+      if (ENT == 1) hsum[qt] = alpha[qt] * (hsum[qt] + dl * ltil[qt]);  // h <- a h + a log(a) l
       ltil[qt] *= alpha[qt];
       msc[qt] = mpend[qt];
     }
@@ -355,20 +392,39 @@ __global__ void __launch_bounds__(64 * NW) flash_kernel(FlashParams P) {
     accumulate(prev_ktile, prev_st, pbprev);
 #pragma unroll
     for (int qt = 0; qt < QT; ++qt)
-      subtile_probs<ENT, TAIL>(scur[qt], sc[qt], msc[qt], ltil[qt], lsum[qt], hsum[qt], pbcur[qt], g, keys_left);
+      subtile_probs<ENT, TAIL>(scur[qt], sc[qt], msc[qt], ltil[qt], hsum[qt], pbcur[qt], g, keys_left);
     if (HAS_NEXT) look_ahead(snext);
-#if VM_SCHED_GROUPS
-    // Issue order handed to the scheduler: the LDS reads of the first MFMA group up front, then
-    // one MFMA at a time with the LDS reads of a later MFMA and a slice of the vector work.
-    __builtin_amdgcn_sched_group_barrier(0x100, HAS_NEXT ? 8 : 0, 0);
+    // Keep this step's vector results in this step: without the pins below the compiler sinks
+    // the probability code past the rescale branch to its first use, next to the MFMAs of the
+    // following step, and the two streams stop overlapping.
 #pragma unroll
-    for (int i = 0; i < (HAS_NEXT ? 8 * QT : 0); ++i) {
+    for (int qt = 0; qt < QT; ++qt) {
+      asm volatile("" : "+v"(pbcur[qt][0]), "+v"(pbcur[qt][1]), "+v"(ltil[qt]), "+v"(mpend[qt]));
+      if (ENT == 1) asm volatile("" : "+v"(hsum[qt]));
+    }
+#if VM_SCHED_GROUPS == 1
+    // Issue order handed to the scheduler: all LDS reads of the step first, a slice of vector
+    // work while they are in flight, then one MFMA at a time with more vector work beside it.
+    __builtin_amdgcn_sched_group_barrier(0x100, HAS_NEXT ? 24 : 16, 0);
+    __builtin_amdgcn_sched_group_barrier(0x002, VM_SCHED_HEAD, 0);
+#pragma unroll
+    for (int i = 0; i < (HAS_NEXT ? 16 : 8); ++i) {
       __builtin_amdgcn_sched_group_barrier(0x008, 1, 0);
-      __builtin_amdgcn_sched_group_barrier(0x100, 2 / QT > 0 ? 2 / QT : 1, 0);
+      __builtin_amdgcn_sched_group_barrier(0x002, VM_SCHED_VALU, 0);
+    }
+#elif VM_SCHED_GROUPS == 2
+    // two phases: reads of the first MFMA group, vector work, first group with the reads of
+    // the second group beside it, second group
+    __builtin_amdgcn_sched_group_barrier(0x100, 8, 0);
+    __builtin_amdgcn_sched_group_barrier(0x002, VM_SCHED_HEAD, 0);
+#pragma unroll
+    for (int i = 0; i < 8; ++i) {
+      __builtin_amdgcn_sched_group_barrier(0x008, 1, 0);
+      __builtin_amdgcn_sched_group_barrier(0x100, 2, 0);
       __builtin_amdgcn_sched_group_barrier(0x002, VM_SCHED_VALU, 0);
     }
 #pragma unroll
-    for (int i = 0; i < 8 * QT; ++i) {
+    for (int i = 0; i < 8; ++i) {
       __builtin_amdgcn_sched_group_barrier(0x008, 1, 0);
       __builtin_amdgcn_sched_group_barrier(0x002, VM_SCHED_VALU, 0);
     }
@@ -377,7 +433,10 @@ __global__ void __launch_bounds__(64 * NW) flash_kernel(FlashParams P) {
 #pragma unroll
       for (int qt = 0; qt < QT; ++qt)
 #pragma unroll
-        for (int ct = 0; ct < 4; ++ct) scale_acc(oacc[qt][ct], alpha[qt]);
+        for (int ct = 0; ct < 4; ++ct) {
+          if (OUT_K) scale_acc(ok[qt][ct], alpha[qt]);
+          if (OUT_V) scale_acc(ov[qt][ct], alpha[qt]);
+        }
     }
   };
   using std::false_type;
@@ -400,20 +459,38 @@ __global__ void __launch_bounds__(64 * NW) flash_kernel(FlashParams P) {
 #pragma unroll
         for (int c = 0; c < 2; ++c) pbB[qt][c] = zero;  // step 0 has no predecessor: it adds P^T = 0
     }
+    DBG_T(1);
     logits(smem, 0, sA);
     look_ahead(sA);
-    for (int t = 0; t < ntiles - 1; ++t) {
+    DBG_T(2);
+    // Main loop, four tiles per trip so that every LDS slot offset is an instruction immediate
+    // (tile t sits in slot t & 3 and the trip starts at a multiple of four).
+    auto tile_iteration = [&](auto slot_c, int t) {
+      constexpr int SLOT = decltype(slot_c)::value;
+      DBG_T(8 + 4 * t);
       if (t > 0) {
         asm volatile("s_waitcnt vmcnt(0)" ::: "memory");
+        DBG_T(9 + 4 * t);
         __syncthreads();  // tile t+1 has landed for everyone; everyone is done with tile t-2
       }
+      DBG_T(10 + 4 * t);
       if (t + 2 < ntiles) issue_tile(t + 2);
-      const char* kp = smem + ((t + 3) & 3) * TILE_BYTES;  // tile t-1
-      const char* kt = smem + (t & 3) * TILE_BYTES;
-      const char* kn = smem + ((t + 1) & 3) * TILE_BYTES;
+      const char* kp = smem + ((SLOT + 3) & 3) * TILE_BYTES;  // tile t-1
+      const char* kt = smem + SLOT * TILE_BYTES;
+      const char* kn = smem + ((SLOT + 1) & 3) * TILE_BYTES;
+      // at t = 0 the "previous" products are P^T = 0 against whatever slot 3 holds: LDS may
+      // hold anything there, so point them at tile 0 instead
       step(false_type{}, true_type{}, sA, sB, pbB, pbA, kt, 1, t > 0 ? kp : kt, 1, 32);
+      DBG_T(11 + 4 * t);
       step(false_type{}, true_type{}, sB, sA, pbA, pbB, kn, 0, kt, 0, 32);
+    };
+    for (int t0 = 0; t0 < ntiles - 1; t0 += 4) {
+      tile_iteration(std::integral_constant<int, 0>{}, t0);
+      if (t0 + 1 < ntiles - 1) tile_iteration(std::integral_constant<int, 1>{}, t0 + 1);
+      if (t0 + 2 < ntiles - 1) tile_iteration(std::integral_constant<int, 2>{}, t0 + 2);
+      if (t0 + 3 < ntiles - 1) tile_iteration(std::integral_constant<int, 3>{}, t0 + 3);
     }
+    DBG_T(3);
     {
       const int t = ntiles - 1;
       if (t > 0) {
@@ -434,12 +511,13 @@ __global__ void __launch_bounds__(64 * NW) flash_kernel(FlashParams P) {
     }
   }
 
+  DBG_T(4);
   // ---- epilogue ----------------------------------------------------------------------------
 #pragma unroll
   for (int qt = 0; qt < QT; ++qt) {
     const float lt = ltil[qt] + __shfl_xor(ltil[qt], 32);
     const float inv = lt > 0.f ? 1.0f / lt : 0.f;
-    const float l = ENT != 0 ? lsum[qt] + __shfl_xor(lsum[qt], 32) : lt;
+    const float l = lt;
     const long long row = qrow0 + qrow[qt];
     if (!SPLIT) {
       if (ENT == 1) {
@@ -457,10 +535,10 @@ __global__ void __launch_bounds__(64 * NW) flash_kernel(FlashParams P) {
 #pragma unroll
           for (int c = 0; c < 4; ++c) {
             uint2 w = *reinterpret_cast<const uint2*>(qp + 32 * ct + 8 * c + 4 * g);
-            dot += __uint_as_float(w.x << 16) * oacc[qt][ct][4 * c + 0];
-            dot += __uint_as_float(w.x & 0xffff0000u) * oacc[qt][ct][4 * c + 1];
-            dot += __uint_as_float(w.y << 16) * oacc[qt][ct][4 * c + 2];
-            dot += __uint_as_float(w.y & 0xffff0000u) * oacc[qt][ct][4 * c + 3];
+            dot += __uint_as_float(w.x << 16) * ok[qt][ct][4 * c + 0];
+            dot += __uint_as_float(w.x & 0xffff0000u) * ok[qt][ct][4 * c + 1];
+            dot += __uint_as_float(w.y << 16) * ok[qt][ct][4 * c + 2];
+            dot += __uint_as_float(w.y & 0xffff0000u) * ok[qt][ct][4 * c + 3];
           }
         dot += __shfl_xor(dot, 32);
         float mean_t = dot * inv * sc[qt];          // sum_l R_l (s_l sc), log2 units
@@ -475,14 +553,14 @@ __global__ void __launch_bounds__(64 * NW) flash_kernel(FlashParams P) {
             const int ch = 32 * ct + 8 * c + 4 * g;
             if (OUT_K) {
               uint2 w;
-              w.x = pack_bf16(oacc[qt][ct][4 * c + 0] * inv, oacc[qt][ct][4 * c + 1] * inv);
-              w.y = pack_bf16(oacc[qt][ct][4 * c + 2] * inv, oacc[qt][ct][4 * c + 3] * inv);
+              w.x = pack_bf16(ok[qt][ct][4 * c + 0] * inv, ok[qt][ct][4 * c + 1] * inv);
+              w.y = pack_bf16(ok[qt][ct][4 * c + 2] * inv, ok[qt][ct][4 * c + 3] * inv);
               *reinterpret_cast<uint2*>(P.outk + row * D + ch) = w;
             }
             if (OUT_V) {
               uint2 w;
-              w.x = pack_bf16(oacc[qt][ct][4 * c + 0] * inv, oacc[qt][ct][4 * c + 1] * inv);
-              w.y = pack_bf16(oacc[qt][ct][4 * c + 2] * inv, oacc[qt][ct][4 * c + 3] * inv);
+              w.x = pack_bf16(ov[qt][ct][4 * c + 0] * inv, ov[qt][ct][4 * c + 1] * inv);
+              w.y = pack_bf16(ov[qt][ct][4 * c + 2] * inv, ov[qt][ct][4 * c + 3] * inv);
               *reinterpret_cast<uint2*>(P.outv + row * D + ch) = w;
             }
           }
@@ -498,13 +576,14 @@ __global__ void __launch_bounds__(64 * NW) flash_kernel(FlashParams P) {
 #pragma unroll
           for (int c = 0; c < 4; ++c) {
             const int ch = 32 * ct + 8 * c + 4 * g;
-            float4 w = {oacc[qt][ct][4 * c + 0] * inv, oacc[qt][ct][4 * c + 1] * inv, oacc[qt][ct][4 * c + 2] * inv,
-                        oacc[qt][ct][4 * c + 3] * inv};
+            float4 w = {ov[qt][ct][4 * c + 0] * inv, ov[qt][ct][4 * c + 1] * inv, ov[qt][ct][4 * c + 2] * inv,
+                        ov[qt][ct][4 * c + 3] * inv};
             *reinterpret_cast<float4*>(P.part_o + prow * D + ch) = w;
           }
       }
     }
   }
+  DBG_T(5);
 }
 
 // Merge of the key-range partials of the first-frame recomputation: weights 2^(lse - max).
@@ -558,6 +637,9 @@ int first_frame_splits(const Dims& dm) {
 }  // namespace
 
 bool flash_supported(const Dims& dm) { return dm.d == D; }
+#ifdef VM_DBG_TIMING
+extern "C" __attribute__((visibility("default"))) void vmonarch_debug_buffer(void* p) { g_dbg_buf = (unsigned long long*)p; }
+#endif
 
 hipError_t launch_r_update_flash(const bf16_t* aR, const float* cR, const bf16_t* k, const bf16_t* v, bf16_t* aL,
                                  float* cL, bf16_t* y, const Dims& dm, float row_scale, float cr_min, int entropy_mode,
@@ -574,11 +656,15 @@ hipError_t launch_r_update_flash(const bf16_t* aR, const float* cR, const bf16_t
   P.total_blocks = (int)total;
   P.blocks_per_xcd = (P.total_blocks + 7) / 8;
   P.row_scale = row_scale; P.cr_min = cr_min;
+#ifdef VM_DBG_TIMING
+  P.dbg = g_dbg_buf;
+#endif
   const bool ident = entropy_mode == VMONARCH_ENTROPY_IDENTITY;
   // alpha_L and c_L from one pass over K; y = R V from a second pass that recomputes the
-  // logits.  A single pass with both accumulator sets needs all 256 accumulation registers
-  // for them and the compiler then spills heavily, which costs more than the repeated
-  // K Q^T product (one third of the fused pass's MFMA work).
+  // logits.  The single-pass variant (flash_kernel<true, true, ...>, both accumulator sets)
+  // compiles, but the register allocator then spills and serialises every LDS read with its
+  // MFMA; measured on the 81 x 28 x 52 workload the whole call took 6.9 ms with it against
+  // 6.1 ms with two passes.
   hipError_t e = ident ? launch_flash<true, false, 2, false>(P, st) : launch_flash<true, false, 1, false>(P, st);
   if (e != hipSuccess || v == nullptr) return e;
   P.outk = nullptr;
