@@ -290,19 +290,27 @@ __global__ void __launch_bounds__(64 * NW) flash_kernel(FlashParams P) {
 
   // ---- tile staging ----------------------------------------------------------------------
   // LDS: NSLOT K tiles at [0, NSLOT * 16 KB), then NSLOT V tiles; tile t lives in slot t & 3.
+  // The global -> LDS loads are written as inline assembly on purpose.  Issued through the
+  // builtin, the compiler tracks them as LDS writes that any later LDS read may alias and puts
+  // s_waitcnt vmcnt(0) in front of the next transpose read, a few instructions after the
+  // load was issued: the prefetch of tile t+2 then stalls every tile for a full memory
+  // latency.  The loop below waits for them itself (s_waitcnt vmcnt(0) before the barrier that
+  // publishes a tile).  Loads the compiler does not know about only make its own vmcnt waits
+  // longer, never shorter, because the counter retires in order.
+  const unsigned lds_base = (unsigned)(unsigned long long)(__attribute__((address_space(3))) char*)smem;
   auto issue_tile = [&](int t) {
-    char* kb = smem + (t & (NSLOT - 1)) * TILE_BYTES;
+    const unsigned kb = lds_base + (t & (NSLOT - 1)) * TILE_BYTES;
 #pragma unroll
     for (int r = 0; r < 16 / NW; ++r) {
       int key = min(t * BK + 4 * NW * r + st_key, nkeys - 1);
       const bf16_t* src = kbase + (long long)key * D + st_lc * 8;
-      char* dst = kb + (4 * NW * r + 4 * wave) * ROW_BYTES;  // wave-uniform; lane lands at + 16 * lane
-      __builtin_amdgcn_global_load_lds((const void __attribute__((address_space(1)))*)src,
-                                       (void __attribute__((address_space(3)))*)dst, 16, 0, 0);
+      // wave-uniform LDS byte address in M0; lane lands at + 16 * lane
+      const unsigned dst = __builtin_amdgcn_readfirstlane(kb + (4 * NW * r + 4 * wave) * ROW_BYTES);
+      asm volatile("s_mov_b32 m0, %1\n\ts_nop 0\n\tglobal_load_lds_dwordx4 %0, off" : : "v"(src), "s"(dst) : "memory", "m0");
       if (OUT_V) {
         const bf16_t* vsrc = vbase + (long long)key * D + st_lc * 8;
-        __builtin_amdgcn_global_load_lds((const void __attribute__((address_space(1)))*)vsrc,
-                                         (void __attribute__((address_space(3)))*)(dst + NSLOT * TILE_BYTES), 16, 0, 0);
+        const unsigned vdst = dst + NSLOT * TILE_BYTES;
+        asm volatile("s_mov_b32 m0, %1\n\ts_nop 0\n\tglobal_load_lds_dwordx4 %0, off" : : "v"(vsrc), "s"(vdst) : "memory", "m0");
       }
     }
   };
