@@ -145,9 +145,9 @@ __device__ __forceinline__ float subtile_max(const f32x16& s) {
 //        relative error on rows dominated by one key.  It also serves as l in the
 //        log-sum-exp and in H = log l - h / l (error ~1e-3 in c_L, one VALU op per score saved);
 //   h  = sum p * t with the unrounded p.
-template <int ENT, bool TAIL>
+template <int ENT>
 __device__ __forceinline__ void subtile_probs(const f32x16& s, float sc, float msc, float& lt, float& h,
-                                              bf16x8 pb[2], int g, int keys_left) {
+                                              bf16x8 pb[2]) {
   typedef __attribute__((__vector_size__(2 * sizeof(__bf16)))) __bf16 bf16x2;
   bf16x2 ones2;
   ones2[0] = (__bf16)1.0f;
@@ -156,10 +156,6 @@ __device__ __forceinline__ void subtile_probs(const f32x16& s, float sc, float m
 #pragma unroll
   for (int r = 0; r < 16; ++r) {
     float t = __builtin_fmaf(s[r], sc, -msc);
-    if (TAIL) {
-      int key = 8 * (r >> 2) + 4 * g + (r & 3);
-      if (key >= keys_left) t = -1000.0f;
-    }
 #ifdef VM_DBG_NO_EXP
     p[r] = t * 1.0e-3f;
 #else
@@ -216,79 +212,15 @@ __global__ void __launch_bounds__(64 * NW) flash_kernel(FlashParams P) {
   const bf16_t* kbase = P.k + ((long long)prob * P.k_rows_per_problem + kbeg) * D;
   const bf16_t* vbase = OUT_V ? P.v + ((long long)prob * P.k_rows_per_problem + kbeg) * D : nullptr;
 
-  // ---- queries: B operand of S^T = K Q^T, kept in registers -------------------------
-  bf16x8 qreg[QT][8];
-  float sc[QT];
-  int qrow[QT];
-  bool qvalid[QT];
-#pragma unroll
-  for (int qt = 0; qt < QT; ++qt) {
-    int r = qb * BQ + wave * (32 * QT) + qt * 32 + ql;
-    qvalid[qt] = r < P.nq;
-    qrow[qt] = qvalid[qt] ? r : P.nq - 1;
-    const bf16_t* qp = P.q + (qrow0 + qrow[qt]) * D + 8 * g;
-#pragma unroll
-    for (int ks = 0; ks < 8; ++ks) qreg[qt][ks] = *reinterpret_cast<const bf16x8*>(qp + 16 * ks);
-    float c = P.cR ? P.cR[qrow0 + qrow[qt]] : 1.0f;
-    c = fmaxf(c, P.cr_min);
-    sc[qt] = P.row_scale * LOG2E / c;
-  }
-
   // ---- LDS addressing ----------------------------------------------------------------
   // staging: global -> LDS directly (global_load_lds_dwordx4).  One wave instruction fills 64
   // consecutive 16-byte slots (4 key rows); slot = key * 16 + physical chunk.  Wave w issues
-  // the instructions for key rows 4 NW r + 4 w .. + 3 (r = 0 .. 16/NW - 1); each lane fetches the logical
-  // chunk that belongs in its slot.  Rows past the end of the key range are clamped to the
-  // last valid row (finite data that the tail mask removes again).
-  const int st_key = 4 * wave + (lane >> 4);             // + 4 NW r
+  // the instructions for key rows 4 NW r + 4 w .. + 3 (r = 0 .. 16/NW - 1); each lane fetches
+  // the logical chunk that belongs in its slot.  Rows past the end of the key range are
+  // clamped to the last valid row: finite data whose logits are pushed to -1e9 again before
+  // they are exponentiated (and which cannot change a row maximum, being copies).
+  const int st_key = 4 * wave + (lane >> 4);  // + 4 NW r
   const int st_lc = (lane & 15) ^ swz(st_key);
-  // row reads (A of S^T): key row = 32 st + ql, logical chunk 2 ks + g
-  int a_off[8];
-#pragma unroll
-  for (int ks = 0; ks < 8; ++ks) a_off[ks] = ql * ROW_BYTES + (((2 * ks + g) ^ swz(ql)) << 4);
-  // transpose reads (A of O^T += X^T P^T): 16-lane group u = lane / 16 -> g = u / 2, channel
-  // half u & 1; lane r' of the group supplies key (r' / 4) and channels 4 (r' & 3) .. + 3
-  int t_off[4][2];
-  {
-    const int rp = lane & 15;
-    const int chh = (lane >> 4) & 1;
-#pragma unroll
-    for (int ct = 0; ct < 4; ++ct)
-#pragma unroll
-      for (int hh = 0; hh < 2; ++hh) {
-        int key = 8 * hh + 4 * g + (rp >> 2);  // + 32 st + 16 c' added as an immediate
-        int lc = 4 * ct + 2 * chh + ((rp >> 1) & 1);
-        t_off[ct][hh] = key * ROW_BYTES + ((lc ^ swz(key)) << 4) + ((rp & 1) << 3);
-      }
-  }
-
-  // ---- accumulators --------------------------------------------------------------------
-  // transpose-read offsets into the V slots (the slot stride of the K part stays an immediate)
-  int tv_off[4][2];
-#pragma unroll
-  for (int ct = 0; ct < 4; ++ct)
-#pragma unroll
-    for (int hh = 0; hh < 2; ++hh) tv_off[ct][hh] = t_off[ct][hh] + NSLOT * TILE_BYTES;
-  // O^T tiles [query tile][32-channel tile]: ok = softmax(z) K (alpha_L), ov = softmax(z) V (y)
-  f32x16 ok[OUT_K ? QT : 1][4], ov[OUT_V ? QT : 1][4];
-#pragma unroll
-  for (int ct = 0; ct < 4; ++ct)
-#pragma unroll
-    for (int r = 0; r < 16; ++r) {
-#pragma unroll
-      for (int qt = 0; qt < (OUT_K ? QT : 1); ++qt) ok[qt][ct][r] = 0.f;
-#pragma unroll
-      for (int qt = 0; qt < (OUT_V ? QT : 1); ++qt) ov[qt][ct][r] = 0.f;
-    }
-  float msc[QT], ltil[QT], hsum[QT];
-#pragma unroll
-  for (int qt = 0; qt < QT; ++qt) {
-    msc[qt] = NEG_BIG;
-    ltil[qt] = 0.f;
-    hsum[qt] = 0.f;
-  }
-
-  // ---- tile staging ----------------------------------------------------------------------
   // LDS: NSLOT K tiles at [0, NSLOT * 16 KB), then NSLOT V tiles; tile t lives in slot t & 3.
   // The global -> LDS loads are written as inline assembly on purpose.  Issued through the
   // builtin, the compiler tracks them as LDS writes that any later LDS read may alias and puts
@@ -314,6 +246,73 @@ __global__ void __launch_bounds__(64 * NW) flash_kernel(FlashParams P) {
       }
     }
   };
+  // the first two tiles go out before anything else so that they travel while Q is fetched
+  if (ntiles > 0) issue_tile(0);
+  if (ntiles > 1) issue_tile(1);
+  // Step 0 has no predecessor and multiplies P^T = 0 with slot 3 of X: clear that slot, LDS
+  // may hold NaN patterns from whoever used it last (0 * NaN would poison the accumulators).
+  {
+    char* x3 = smem + (OUT_K ? 0 : NSLOT * TILE_BYTES) + 3 * TILE_BYTES;
+    const uint4 z = {0u, 0u, 0u, 0u};
+#pragma unroll
+    for (int r = 0; r < TILE_BYTES / (16 * 64 * NW); ++r) *reinterpret_cast<uint4*>(x3 + (r * 64 * NW + tid) * 16) = z;
+  }
+
+  // ---- queries: B operand of S^T = K Q^T, kept in registers -------------------------
+  bf16x8 qreg[QT][8];
+  float sc[QT];
+  int qrow[QT];
+  bool qvalid[QT];
+#pragma unroll
+  for (int qt = 0; qt < QT; ++qt) {
+    int r = qb * BQ + wave * (32 * QT) + qt * 32 + ql;
+    qvalid[qt] = r < P.nq;
+    qrow[qt] = qvalid[qt] ? r : P.nq - 1;
+    const bf16_t* qp = P.q + (qrow0 + qrow[qt]) * D + 8 * g;
+#pragma unroll
+    for (int ks = 0; ks < 8; ++ks) qreg[qt][ks] = *reinterpret_cast<const bf16x8*>(qp + 16 * ks);
+    float c = P.cR ? P.cR[qrow0 + qrow[qt]] : 1.0f;
+    c = fmaxf(c, P.cr_min);
+    sc[qt] = P.row_scale * LOG2E / c;
+  }
+
+  // row reads (A of S^T): key row = 32 st + ql, logical chunk 2 ks + g
+  int a_off[8];
+#pragma unroll
+  for (int ks = 0; ks < 8; ++ks) a_off[ks] = ql * ROW_BYTES + (((2 * ks + g) ^ swz(ql)) << 4);
+  // transpose reads (A of O^T += X^T P^T): 16-lane group u = lane / 16 -> g = u / 2, channel
+  // half u & 1; lane r' of the group supplies key (r' / 4) and channels 4 (r' & 3) .. + 3.
+  // For X = V the offsets point into the V slots.
+  int t_off[4][2];
+  {
+    const int rp = lane & 15;
+    const int chh = (lane >> 4) & 1;
+#pragma unroll
+    for (int ct = 0; ct < 4; ++ct)
+#pragma unroll
+      for (int hh = 0; hh < 2; ++hh) {
+        int key = 8 * hh + 4 * g + (rp >> 2);  // + 32 st + 16 c' added as an immediate
+        int lc = 4 * ct + 2 * chh + ((rp >> 1) & 1);
+        t_off[ct][hh] = key * ROW_BYTES + ((lc ^ swz(key)) << 4) + ((rp & 1) << 3) + (OUT_K ? 0 : NSLOT * TILE_BYTES);
+      }
+  }
+
+  // ---- accumulators and statistics -------------------------------------------------------
+  static_assert(OUT_K != OUT_V, "one accumulator set per pass (see launch_r_update_flash)");
+  f32x16 oacc[QT][4];  // O^T tiles: [query tile][32-channel tile]
+#pragma unroll
+  for (int qt = 0; qt < QT; ++qt)
+#pragma unroll
+    for (int ct = 0; ct < 4; ++ct)
+#pragma unroll
+      for (int r = 0; r < 16; ++r) oacc[qt][ct][r] = 0.f;
+  float msc[QT], ltil[QT], hsum[QT];
+#pragma unroll
+  for (int qt = 0; qt < QT; ++qt) {
+    msc[qt] = NEG_BIG;
+    ltil[qt] = 0.f;
+    hsum[qt] = 0.f;
+  }
 
   // Software pipeline over 32-key sub-tiles n = 0, 1, ...  Step n carries two independent
   // instruction streams:
@@ -324,6 +323,9 @@ __global__ void __launch_bounds__(64 * NW) flash_kernel(FlashParams P) {
   // rescales the scalar statistics at the top of the step, before they are added to, and the
   // accumulators at the bottom, after the products of sub-tile n-1 (computed against the old
   // reference) have been issued and before those of sub-tile n are.
+  // Every step is the same code: the step after the last sub-tile's predecessor forms the
+  // logits of a sub-tile that does not exist (from whatever its LDS slot holds) and nobody
+  // reads them; a ragged last tile only adds one uniform branch at the top of its two steps.
   auto logits = [&](const char* ktile, int st, f32x16 (&sacc)[QT]) {
 #pragma unroll
     for (int qt = 0; qt < QT; ++qt)
@@ -341,29 +343,23 @@ __global__ void __launch_bounds__(64 * NW) flash_kernel(FlashParams P) {
         sacc[qt] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(a, qreg[qt][ks], sacc[qt], 0, 0, 0);
     }
   };
-  // O^T += X^T P^T for sub-tile `st` of the tile whose K slot is `ktile` (X = K and/or V)
+  // O^T += X^T P^T for sub-tile `st` of the tile whose K slot is `ktile`
   auto accumulate = [&](const char* ktile, int st, bf16x8 (&pb)[QT][2]) {
 #pragma unroll
     for (int c = 0; c < 2; ++c) {
       const int koff = (st * 32 + c * 16) * ROW_BYTES;
 #pragma unroll
       for (int ct = 0; ct < 4; ++ct) {
-        if (OUT_K) {
-          bf16x4 lo = lds_read_tr(ktile + koff + t_off[ct][0]);
-          bf16x4 hi = lds_read_tr(ktile + koff + t_off[ct][1]);
-          bf16x8 a = __builtin_shufflevector(lo, hi, 0, 1, 2, 3, 4, 5, 6, 7);
+#ifdef VM_DBG_NO_LDS_PV
+        bf16x8 a = qreg[0][(2 * ct + c) & 7];
+#else
+        bf16x4 lo = lds_read_tr(ktile + koff + t_off[ct][0]);
+        bf16x4 hi = lds_read_tr(ktile + koff + t_off[ct][1]);
+        bf16x8 a = __builtin_shufflevector(lo, hi, 0, 1, 2, 3, 4, 5, 6, 7);
+#endif
 #pragma unroll
-          for (int qt = 0; qt < QT; ++qt)
-            ok[qt][ct] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(a, pb[qt][c], ok[qt][ct], 0, 0, 0);
-        }
-        if (OUT_V) {
-          bf16x4 lo = lds_read_tr(ktile + koff + tv_off[ct][0]);
-          bf16x4 hi = lds_read_tr(ktile + koff + tv_off[ct][1]);
-          bf16x8 a = __builtin_shufflevector(lo, hi, 0, 1, 2, 3, 4, 5, 6, 7);
-#pragma unroll
-          for (int qt = 0; qt < QT; ++qt)
-            ov[qt][ct] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(a, pb[qt][c], ov[qt][ct], 0, 0, 0);
-        }
+        for (int qt = 0; qt < QT; ++qt)
+          oacc[qt][ct] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(a, pb[qt][c], oacc[qt][ct], 0, 0, 0);
       }
     }
   };
@@ -381,11 +377,18 @@ __global__ void __launch_bounds__(64 * NW) flash_kernel(FlashParams P) {
 #pragma unroll
     for (int qt = 0; qt < QT; ++qt) mpend[qt] = moved ? fmaxf(msc[qt], cand[qt]) : msc[qt];
   };
-  auto step = [&](auto tail_c, auto next_c, f32x16 (&scur)[QT], f32x16 (&snext)[QT], bf16x8 (&pbprev)[QT][2],
-                  bf16x8 (&pbcur)[QT][2], const char* next_ktile, int next_st, const char* prev_ktile, int prev_st,
-                  int keys_left) {
-    constexpr bool TAIL = decltype(tail_c)::value;
-    constexpr bool HAS_NEXT = decltype(next_c)::value;
+  auto step = [&](f32x16 (&scur)[QT], f32x16 (&snext)[QT], bf16x8 (&pbprev)[QT][2], bf16x8 (&pbcur)[QT][2],
+                  const char* next_ktile, int next_st, const char* prev_ktile, int prev_st, int keys_left) {
+    if (keys_left < 32) {
+      // ragged end of the key range: rows keys_left .. 31 of this sub-tile are copies of the
+      // last valid row; push their logits far down so that they get probability zero
+#pragma unroll
+      for (int r = 0; r < 16; ++r) {
+        const float off = (8 * (r >> 2) + 4 * g + (r & 3)) >= keys_left ? -1.0e9f : 0.f;
+#pragma unroll
+        for (int qt = 0; qt < QT; ++qt) scur[qt][r] += off;
+      }
+    }
     const bool moved_now = moved;
     float alpha[QT];
 #pragma unroll
@@ -396,12 +399,11 @@ __global__ void __launch_bounds__(64 * NW) flash_kernel(FlashParams P) {
       ltil[qt] *= alpha[qt];
       msc[qt] = mpend[qt];
     }
-    if (HAS_NEXT) logits(next_ktile, next_st, snext);
+    logits(next_ktile, next_st, snext);
     accumulate(prev_ktile, prev_st, pbprev);
 #pragma unroll
-    for (int qt = 0; qt < QT; ++qt)
-      subtile_probs<ENT, TAIL>(scur[qt], sc[qt], msc[qt], ltil[qt], hsum[qt], pbcur[qt], g, keys_left);
-    if (HAS_NEXT) look_ahead(snext);
+    for (int qt = 0; qt < QT; ++qt) subtile_probs<ENT>(scur[qt], sc[qt], msc[qt], ltil[qt], hsum[qt], pbcur[qt]);
+    look_ahead(snext);
     // Keep this step's vector results in this step: without the pins below the compiler sinks
     // the probability code past the rescale branch to its first use, next to the MFMAs of the
     // following step, and the two streams stop overlapping.
@@ -410,19 +412,10 @@ __global__ void __launch_bounds__(64 * NW) flash_kernel(FlashParams P) {
       asm volatile("" : "+v"(pbcur[qt][0]), "+v"(pbcur[qt][1]), "+v"(ltil[qt]), "+v"(mpend[qt]));
       if (ENT == 1) asm volatile("" : "+v"(hsum[qt]));
     }
-#if VM_SCHED_GROUPS == 1
-    // Issue order handed to the scheduler: all LDS reads of the step first, a slice of vector
-    // work while they are in flight, then one MFMA at a time with more vector work beside it.
-    __builtin_amdgcn_sched_group_barrier(0x100, HAS_NEXT ? 24 : 16, 0);
-    __builtin_amdgcn_sched_group_barrier(0x002, VM_SCHED_HEAD, 0);
-#pragma unroll
-    for (int i = 0; i < (HAS_NEXT ? 16 : 8); ++i) {
-      __builtin_amdgcn_sched_group_barrier(0x008, 1, 0);
-      __builtin_amdgcn_sched_group_barrier(0x002, VM_SCHED_VALU, 0);
-    }
-#elif VM_SCHED_GROUPS == 2
-    // two phases: reads of the first MFMA group, vector work, first group with the reads of
-    // the second group beside it, second group
+#if VM_SCHED_GROUPS == 2
+    // Issue order handed to the scheduler: the LDS reads of the first MFMA group, a slice of
+    // vector work while they are in flight, the first group one MFMA at a time with the
+    // reads of the second group and more vector work beside it, then the second group.
     __builtin_amdgcn_sched_group_barrier(0x100, 8, 0);
     __builtin_amdgcn_sched_group_barrier(0x002, VM_SCHED_HEAD, 0);
 #pragma unroll
@@ -441,21 +434,15 @@ __global__ void __launch_bounds__(64 * NW) flash_kernel(FlashParams P) {
 #pragma unroll
       for (int qt = 0; qt < QT; ++qt)
 #pragma unroll
-        for (int ct = 0; ct < 4; ++ct) {
-          if (OUT_K) scale_acc(ok[qt][ct], alpha[qt]);
-          if (OUT_V) scale_acc(ov[qt][ct], alpha[qt]);
-        }
+        for (int ct = 0; ct < 4; ++ct) scale_acc(oacc[qt][ct], alpha[qt]);
     }
   };
-  using std::false_type;
-  using std::true_type;
 
+  DBG_T(1);
   if (ntiles > 0) {
     // Four LDS slots, tile t in slot t & 3: during tile t the products of the last sub-tile of
     // tile t-1 are still outstanding, tile t+1 is resident (its first sub-tile is needed one
     // step ahead) and tile t+2 is in flight.
-    issue_tile(0);
-    if (ntiles > 1) issue_tile(1);
     asm volatile("s_waitcnt vmcnt(0)" ::: "memory");
     __syncthreads();
     f32x16 sA[QT], sB[QT];
@@ -467,12 +454,12 @@ __global__ void __launch_bounds__(64 * NW) flash_kernel(FlashParams P) {
 #pragma unroll
         for (int c = 0; c < 2; ++c) pbB[qt][c] = zero;  // step 0 has no predecessor: it adds P^T = 0
     }
-    DBG_T(1);
     logits(smem, 0, sA);
     look_ahead(sA);
     DBG_T(2);
-    // Main loop, four tiles per trip so that every LDS slot offset is an instruction immediate
-    // (tile t sits in slot t & 3 and the trip starts at a multiple of four).
+    const int last_left = nkeys - (ntiles - 1) * BK;  // 1..64 keys in the last tile
+    // Four tiles per trip so that every LDS slot offset is an instruction immediate (tile t
+    // sits in slot t & 3 and a trip starts at a multiple of four).
     auto tile_iteration = [&](auto slot_c, int t) {
       constexpr int SLOT = decltype(slot_c)::value;
       DBG_T(8 + 4 * t);
@@ -486,52 +473,37 @@ __global__ void __launch_bounds__(64 * NW) flash_kernel(FlashParams P) {
       const char* kp = smem + ((SLOT + 3) & 3) * TILE_BYTES;  // tile t-1
       const char* kt = smem + SLOT * TILE_BYTES;
       const char* kn = smem + ((SLOT + 1) & 3) * TILE_BYTES;
-      // at t = 0 the "previous" products are P^T = 0 against whatever slot 3 holds: LDS may
-      // hold anything there, so point them at tile 0 instead
-      step(false_type{}, true_type{}, sA, sB, pbB, pbA, kt, 1, t > 0 ? kp : kt, 1, 32);
+      const int left0 = t == ntiles - 1 ? last_left : 64;
+      step(sA, sB, pbB, pbA, kt, 1, kp, 1, left0);  // at t = 0: P^T = 0 against the cleared slot 3
       DBG_T(11 + 4 * t);
-      step(false_type{}, true_type{}, sB, sA, pbA, pbB, kn, 0, kt, 0, 32);
+      step(sB, sA, pbA, pbB, kn, 0, kt, 0, left0 - 32);
     };
-    for (int t0 = 0; t0 < ntiles - 1; t0 += 4) {
+    for (int t0 = 0; t0 < ntiles; t0 += 4) {
       tile_iteration(std::integral_constant<int, 0>{}, t0);
-      if (t0 + 1 < ntiles - 1) tile_iteration(std::integral_constant<int, 1>{}, t0 + 1);
-      if (t0 + 2 < ntiles - 1) tile_iteration(std::integral_constant<int, 2>{}, t0 + 2);
-      if (t0 + 3 < ntiles - 1) tile_iteration(std::integral_constant<int, 3>{}, t0 + 3);
+      if (t0 + 1 < ntiles) tile_iteration(std::integral_constant<int, 1>{}, t0 + 1);
+      if (t0 + 2 < ntiles) tile_iteration(std::integral_constant<int, 2>{}, t0 + 2);
+      if (t0 + 3 < ntiles) tile_iteration(std::integral_constant<int, 3>{}, t0 + 3);
     }
     DBG_T(3);
-    {
-      const int t = ntiles - 1;
-      if (t > 0) {
-        asm volatile("s_waitcnt vmcnt(0)" ::: "memory");
-        __syncthreads();
-      }
-      const char* kp = smem + ((t + 3) & 3) * TILE_BYTES;
-      const char* kt = smem + (t & 3) * TILE_BYTES;
-      const int left = nkeys - t * BK;  // 1..64 keys in the last tile
-      if (left == BK) {
-        step(false_type{}, true_type{}, sA, sB, pbB, pbA, kt, 1, t > 0 ? kp : kt, 1, 32);
-        step(false_type{}, false_type{}, sB, sA, pbA, pbB, kt, 0, kt, 0, 32);
-      } else {
-        step(true_type{}, true_type{}, sA, sB, pbB, pbA, kt, 1, t > 0 ? kp : kt, 1, left);
-        step(true_type{}, false_type{}, sB, sA, pbA, pbB, kt, 0, kt, 0, left - 32);
-      }
-      accumulate(kt, 1, pbB);  // drain: the products of the last sub-tile
-    }
+    accumulate(smem + ((ntiles - 1) & 3) * TILE_BYTES, 1, pbB);  // drain: the products of the last sub-tile
   }
 
   DBG_T(4);
   // ---- epilogue ----------------------------------------------------------------------------
+  // Normalised rows are staged in LDS (each wave owns the 32 * QT rows it computed, swizzled
+  // like the key tiles) and leave as whole 256-byte rows, 16 bytes per lane.
+  __syncthreads();  // every wave is done with the key/value tiles
+  char* stage = smem + wave * (32 * QT * ROW_BYTES);
 #pragma unroll
   for (int qt = 0; qt < QT; ++qt) {
     const float lt = ltil[qt] + __shfl_xor(ltil[qt], 32);
     const float inv = lt > 0.f ? 1.0f / lt : 0.f;
-    const float l = lt;
     const long long row = qrow0 + qrow[qt];
     if (!SPLIT) {
       if (ENT == 1) {
         // App. B: H = log S - L / S; here in base-2 units, c_L = -H
         float h = hsum[qt] + __shfl_xor(hsum[qt], 32);
-        float H2 = __log2f(l) - h / l;
+        float H2 = __log2f(lt) - h * inv;
         if (qvalid[qt] && g == 0) P.cl[row] = -LN2 * H2;
       }
       if (ENT == 2) {
@@ -543,36 +515,26 @@ __global__ void __launch_bounds__(64 * NW) flash_kernel(FlashParams P) {
 #pragma unroll
           for (int c = 0; c < 4; ++c) {
             uint2 w = *reinterpret_cast<const uint2*>(qp + 32 * ct + 8 * c + 4 * g);
-            dot += __uint_as_float(w.x << 16) * ok[qt][ct][4 * c + 0];
-            dot += __uint_as_float(w.x & 0xffff0000u) * ok[qt][ct][4 * c + 1];
-            dot += __uint_as_float(w.y << 16) * ok[qt][ct][4 * c + 2];
-            dot += __uint_as_float(w.y & 0xffff0000u) * ok[qt][ct][4 * c + 3];
+            dot += __uint_as_float(w.x << 16) * oacc[qt][ct][4 * c + 0];
+            dot += __uint_as_float(w.x & 0xffff0000u) * oacc[qt][ct][4 * c + 1];
+            dot += __uint_as_float(w.y << 16) * oacc[qt][ct][4 * c + 2];
+            dot += __uint_as_float(w.y & 0xffff0000u) * oacc[qt][ct][4 * c + 3];
           }
         dot += __shfl_xor(dot, 32);
         float mean_t = dot * inv * sc[qt];          // sum_l R_l (s_l sc), log2 units
-        float lse2 = msc[qt] + __log2f(l);
+        float lse2 = msc[qt] + __log2f(lt);
         if (qvalid[qt] && g == 0) P.cl[row] = LN2 * (mean_t - lse2);
       }
-      if (qvalid[qt]) {
+      // lane (q, g) holds channels 32 ct + 8 c + 4 g .. + 3 of query q: 8-byte pieces
 #pragma unroll
-        for (int ct = 0; ct < 4; ++ct)
+      for (int ct = 0; ct < 4; ++ct)
 #pragma unroll
-          for (int c = 0; c < 4; ++c) {
-            const int ch = 32 * ct + 8 * c + 4 * g;
-            if (OUT_K) {
-              uint2 w;
-              w.x = pack_bf16(ok[qt][ct][4 * c + 0] * inv, ok[qt][ct][4 * c + 1] * inv);
-              w.y = pack_bf16(ok[qt][ct][4 * c + 2] * inv, ok[qt][ct][4 * c + 3] * inv);
-              *reinterpret_cast<uint2*>(P.outk + row * D + ch) = w;
-            }
-            if (OUT_V) {
-              uint2 w;
-              w.x = pack_bf16(ov[qt][ct][4 * c + 0] * inv, ov[qt][ct][4 * c + 1] * inv);
-              w.y = pack_bf16(ov[qt][ct][4 * c + 2] * inv, ov[qt][ct][4 * c + 3] * inv);
-              *reinterpret_cast<uint2*>(P.outv + row * D + ch) = w;
-            }
-          }
-      }
+        for (int c = 0; c < 4; ++c) {
+          uint2 w;
+          w.x = pack_bf16(oacc[qt][ct][4 * c + 0] * inv, oacc[qt][ct][4 * c + 1] * inv);
+          w.y = pack_bf16(oacc[qt][ct][4 * c + 2] * inv, oacc[qt][ct][4 * c + 3] * inv);
+          *reinterpret_cast<uint2*>(stage + (32 * qt + ql) * ROW_BYTES + (((4 * ct + c) ^ swz(ql)) << 4) + 8 * g) = w;
+        }
     } else {
       // partial result of this key range: normalised output and log2-sum-exp
       if (qvalid[qt]) {
@@ -584,10 +546,27 @@ __global__ void __launch_bounds__(64 * NW) flash_kernel(FlashParams P) {
 #pragma unroll
           for (int c = 0; c < 4; ++c) {
             const int ch = 32 * ct + 8 * c + 4 * g;
-            float4 w = {ov[qt][ct][4 * c + 0] * inv, ov[qt][ct][4 * c + 1] * inv, ov[qt][ct][4 * c + 2] * inv,
-                        ov[qt][ct][4 * c + 3] * inv};
+            float4 w = {oacc[qt][ct][4 * c + 0] * inv, oacc[qt][ct][4 * c + 1] * inv, oacc[qt][ct][4 * c + 2] * inv,
+                        oacc[qt][ct][4 * c + 3] * inv};
             *reinterpret_cast<float4*>(P.part_o + prow * D + ch) = w;
           }
+      }
+    }
+  }
+  if (!SPLIT) {
+    // the staged rows are private to the wave: no barrier, only the LDS writes above must land
+    __builtin_amdgcn_s_waitcnt(0xc07f);  // lgkmcnt(0)
+    __builtin_amdgcn_wave_barrier();
+    bf16_t* dst = OUT_K ? P.outk : P.outv;
+    const int row_first = qb * BQ + wave * (32 * QT);
+#pragma unroll
+    for (int ps = 0; ps < 8 * QT; ++ps) {
+      const int lr = ps * 4 + (lane >> 4);  // row within the wave's block
+      const int pc = lane & 15;
+      const int lc = pc ^ swz(lr);
+      if (row_first + lr < P.nq) {
+        uint4 w = *reinterpret_cast<const uint4*>(stage + lr * ROW_BYTES + pc * 16);
+        *reinterpret_cast<uint4*>(dst + (qrow0 + row_first + lr) * D + lc * 8) = w;
       }
     }
   }
