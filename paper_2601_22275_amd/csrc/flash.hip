@@ -190,8 +190,10 @@ __global__ void __launch_bounds__(64 * NW) flash_kernel(FlashParams P) {
   const int per_problem = P.nqb * P.nsplit;
   const int prob = wid / per_problem;
   const int rem = wid - prob * per_problem;
-  const int qb = rem / P.nsplit;
-  const int split = rem - qb * P.nsplit;
+  // the query blocks of one key range are neighbours: they stream the same K and V tiles at
+  // the same time and share them through the XCD's L2
+  const int split = rem / P.nqb;
+  const int qb = rem - split * P.nqb;
 
   const int tid = threadIdx.x;
   const int wave = tid >> 6;
