@@ -53,6 +53,17 @@ def test_wan_480p_clip_sampled_positions(env):
     _run_workload(env, "wan1.3b-480p", [0, 7], 48, 1)
 
 
+def test_wan_720p_clip_sampled_positions(env):
+    """b = 3600 (15 query blocks, ragged), T = 21 padded to 32 in the temporal pass; 2 of the 40 heads."""
+    _run_workload(env, "wan14b-720p", [0, 39], 16, 3)
+
+
+def test_million_token_stress_single_head(env):
+    """N = 991,440 tokens: b = 12,240 keys per frame (192 key tiles, ragged), one sweep, no
+    recomputation; one of the 12 heads (row offsets beyond 2^31 bytes within the head)."""
+    _run_workload(env, "stress-1m", [5], 8, 4)
+
+
 def test_headline_long_video_sampled_positions_and_invariants(env):
     torch, binding, dev = env
     tq, tk, tv, out, wl = _run_workload(env, "long-81x28x52", [0, 5, 11], 24, 2)
