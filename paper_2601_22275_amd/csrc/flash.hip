@@ -2,9 +2,9 @@
 // gfx950: the R-update (Eq. R + Eq. alpha_L/c_L, computed as Alg. 1 with the running
 // max / sum / entropy of App. B) and the first-frame recomputation (Sec. 3.3).
 //
-// One workgroup = 4 waves = 256 query rows; each wave owns 64 query rows (two 32-wide
-// tiles) for the whole key loop.  Keys (and values) stream through LDS in 64-row tiles,
-// double buffered.  Both contractions use v_mfma_f32_32x32x16_bf16:
+// One workgroup = 8 waves = 256 query rows; each wave owns 32 query rows for the whole key
+// loop.  Keys (and values) stream through LDS in 64-row tiles, four slots per tensor, loaded
+// two tiles ahead.  Both contractions use v_mfma_f32_32x32x16_bf16:
 //
 //   S^T = K Q^T     A = K rows read from LDS (ds_read_b128), B = Q^T held in registers.
 //                   In the result lane (q, g) holds the logits of query q for 16 of the 32
