@@ -23,8 +23,11 @@
  *   - Return value: 0 on success, a negative VMONARCH_ERR_* otherwise; nothing is
  *     launched when validation fails.  vmonarch_last_error() describes the last failure
  *     of the calling thread.  No exception crosses this boundary.
- *   - d <= 256 for every entry point.  bf16 with d == 128 and T <= 128 runs on the MFMA
- *     kernels; other shapes run on slower plain-ALU kernels with the same results.
+ *   - d <= 256 for every entry point.  bf16 with d == 128 or d == 64 runs on the MFMA
+ *     kernels (the temporal pass additionally needs T <= 128); other shapes run on slower
+ *     plain-ALU kernels with the same results.
+ *   - (T, Hs, Ws) only enter as m = T blocks of b = Hs*Ws tokens: a general Monarch split
+ *     (m, b) of a sequence that is no video is T = m, Hs = 1, Ws = b.
  */
 #ifndef VMONARCH_H_
 #define VMONARCH_H_

@@ -28,6 +28,35 @@ template <typename E> __device__ __forceinline__ void store_f(E* p, float x);
 template <> __device__ __forceinline__ void store_f<float>(float* p, float x) { *p = x; }
 template <> __device__ __forceinline__ void store_f<bf16_t>(bf16_t* p, float x) { *p = f32_to_bf16(x); }
 
+// Geometry of a bf16 row tile in LDS for head dimension D (64 or 128), shared by the MFMA
+// kernels.  A row is D/8 chunks of 16 bytes; chunk c of row r is stored at chunk c ^ swz(r).
+// swz depends on r & 15 only, so adding a multiple of 16 rows to an address is plain
+// arithmetic.  It is chosen so that the two read patterns of the 32x32x16 MFMA operands
+// spread over all 64 banks:
+//   row reads (ds_read_b128, 16 consecutive rows, one logical chunk): 16 distinct 16-byte
+//     bank groups.  D = 128: a row is the whole 256-byte bank window and swz is a bijection of
+//     the 16 rows.  D = 64: two rows share the window and swz is a bijection of the 8 row pairs;
+//   transpose reads (ds_read_b64_tr_b16, 8 consecutive rows x 4 consecutive chunks): every
+//     bank group twice, the minimum for 512 bytes.
+template <int D>
+struct RowGeo {
+  static_assert(D == 64 || D == 128, "head dimensions with an MFMA path");
+  static constexpr int ROW_BYTES = D * 2;
+  static constexpr int CH = D / 8;    // 16-byte chunks per row
+  static constexpr int KS = D / 16;   // k-steps of a contraction over d
+  static constexpr int CT = D / 32;   // 32-channel tiles of an output row
+  static constexpr int RPI = 1024 / ROW_BYTES;  // rows covered by one 64-lane x 16-byte access
+  __device__ static __forceinline__ int swz(int row) {
+    if (D == 128) {
+      const int x = row & 15;
+      return ((x & 3) << 2) | (x >> 2);
+    } else {
+      const int p = (row >> 1) & 7;
+      return ((p & 1) << 2) | (p >> 1);
+    }
+  }
+};
+
 // Problem description handed to every launcher.
 struct Dims {
   int BH;     // B * heads
@@ -50,7 +79,7 @@ hipError_t launch_first_frame_generic(const E* q, const E* k, const E* v, E* out
 hipError_t launch_permute_tokens(const void* in, void* out, const Dims& dm, int row_bytes, int to_pos_major,
                                  hipStream_t st);
 
-// flash.hip : bf16 MFMA blocked-softmax kernels (d == 128)
+// flash.hip : bf16 MFMA blocked-softmax kernels (d == 64 or 128)
 bool flash_supported(const Dims& dm);
 hipError_t launch_r_update_flash(const bf16_t* aR, const float* cR, const bf16_t* k, const bf16_t* v, bf16_t* aL,
                                  float* cL, bf16_t* y, const Dims& dm, float row_scale, float cr_min,
@@ -59,7 +88,7 @@ size_t first_frame_flash_scratch_bytes(const Dims& dm);
 hipError_t launch_first_frame_flash(const bf16_t* q, const bf16_t* k, const bf16_t* v, bf16_t* out, void* scratch,
                                     size_t scratch_bytes, const Dims& dm, hipStream_t st);
 
-// lpass.hip : bf16 MFMA temporal kernels (d == 128, T <= 128)
+// lpass.hip : bf16 MFMA temporal kernels (d == 64 or 128, T <= 128)
 bool lpass_supported(const Dims& dm);
 hipError_t launch_l_update_mfma(const bf16_t* q, const bf16_t* aL, const float* cL, const bf16_t* y, bf16_t* aR,
                                 float* cR, bf16_t* out, const Dims& dm, float q_scale, hipStream_t st);

@@ -15,9 +15,9 @@
 //                   B = P^T, which is the S^T accumulator converted to bf16 in place:
 //                   eight consecutive accumulator registers are exactly one B operand.
 //
-// LDS rows are 256 B (d = 128); the 16-byte chunk c of key row r is stored at chunk
-// c ^ swz(r) so that both the row-wise b128 reads and the transpose reads spread over
-// all banks.
+// The kernels are instantiated for d = 128 and d = 64.  The 16-byte chunk c of key row r is
+// stored at chunk c ^ swz(r) (RowGeo in common.h) so that both the row-wise b128 reads and
+// the transpose reads spread over all banks.
 #include "../../include/vmonarch.h"
 #include <type_traits>
 
@@ -27,7 +27,6 @@ namespace vm {
 
 namespace {
 
-constexpr int D = 128;          // head dimension handled here
 constexpr int BK = 64;          // key rows per LDS tile
 #ifndef VM_FLASH_QT
 #define VM_FLASH_QT 1           // 32-query tiles per wave
@@ -39,8 +38,6 @@ constexpr int QT = VM_FLASH_QT;
 constexpr int NW = VM_FLASH_NW;
 constexpr int BQ = 32 * QT * NW;  // query rows per workgroup
 constexpr int NSLOT = 4;          // LDS tile slots per tensor
-constexpr int ROW_BYTES = D * 2;
-constexpr int TILE_BYTES = BK * ROW_BYTES;  // 16 KB
 constexpr float LOG2E = 1.4426950408889634f;
 constexpr float LN2 = 0.6931471805599453f;
 constexpr float RESCALE_TH = 8.0f;  // rescale the accumulators only when a row max grows by 2^8
@@ -86,11 +83,6 @@ unsigned long long* g_dbg_buf = nullptr;
 #else
 #define DBG_T(slot) do { } while (0)
 #endif
-
-__device__ __forceinline__ int swz(int key) {
-  int x = key & 15;
-  return ((x & 3) << 2) | (x >> 2);
-}
 
 __device__ __forceinline__ bf16x8 lds_read_b128(const char* p) { return *reinterpret_cast<const bf16x8*>(p); }
 
@@ -177,9 +169,17 @@ __device__ __forceinline__ void subtile_probs(const f32x16& s, float sc, float m
   }
 }
 
-template <bool OUT_K, bool OUT_V, int ENT, bool SPLIT>
+template <int D, bool OUT_K, bool OUT_V, int ENT, bool SPLIT>
 __global__ void __launch_bounds__(64 * NW) flash_kernel(FlashParams P) {
-  extern __shared__ __attribute__((aligned(16))) char smem[];  // [K|V][NSLOT][64 rows][256 B]
+  using G = RowGeo<D>;
+  constexpr int ROW_BYTES = G::ROW_BYTES;
+  constexpr int TILE_BYTES = BK * ROW_BYTES;  // 16 KB (d = 128) or 8 KB (d = 64)
+  constexpr int KS = G::KS;                   // k-steps of S^T = K Q^T
+  constexpr int CT = G::CT;                   // 32-channel tiles of an output row
+  constexpr int CH = G::CH;                   // 16-byte chunks per row
+  constexpr int RPI = G::RPI;                 // rows filled by one 64-lane global -> LDS load
+  auto swz = [](int row) { return G::swz(row); };
+  extern __shared__ __attribute__((aligned(16))) char smem[];  // [K|V][NSLOT][64 rows][2 D bytes]
 
   // XCD-aware placement: hardware deals workgroups to the 8 XCDs round-robin, so give each
   // XCD one contiguous range of work items; the query blocks of one (head, frame) then share
@@ -216,13 +216,14 @@ __global__ void __launch_bounds__(64 * NW) flash_kernel(FlashParams P) {
 
   // ---- LDS addressing ----------------------------------------------------------------
   // staging: global -> LDS directly (global_load_lds_dwordx4).  One wave instruction fills 64
-  // consecutive 16-byte slots (4 key rows); slot = key * 16 + physical chunk.  Wave w issues
-  // the instructions for key rows 4 NW r + 4 w .. + 3 (r = 0 .. 16/NW - 1); each lane fetches
-  // the logical chunk that belongs in its slot.  Rows past the end of the key range are
+  // consecutive 16-byte slots (RPI key rows); slot = key * CH + physical chunk.  Wave w issues
+  // the instructions for key rows RPI (NW r + w) .. + RPI - 1 (r = 0 .. BK / (RPI NW) - 1);
+  // each lane fetches the logical chunk that belongs in its slot.  Rows past the end of the key range are
   // clamped to the last valid row: finite data whose logits are pushed to -1e9 again before
   // they are exponentiated (and which cannot change a row maximum, being copies).
-  const int st_key = 4 * wave + (lane >> 4);  // + 4 NW r
-  const int st_lc = (lane & 15) ^ swz(st_key);
+  static_assert(BK % (RPI * NW) == 0, "every wave issues the same number of loads per tile");
+  const int st_key = RPI * wave + lane / CH;  // + RPI NW r
+  const int st_lc = (lane % CH) ^ swz(st_key);
   // LDS: NSLOT K tiles at [0, NSLOT * 16 KB), then NSLOT V tiles; tile t lives in slot t & 3.
   // The global -> LDS loads are written as inline assembly on purpose.  Issued through the
   // builtin, the compiler tracks them as LDS writes that any later LDS read may alias and puts
@@ -235,11 +236,11 @@ __global__ void __launch_bounds__(64 * NW) flash_kernel(FlashParams P) {
   auto issue_tile = [&](int t) {
     const unsigned kb = lds_base + (t & (NSLOT - 1)) * TILE_BYTES;
 #pragma unroll
-    for (int r = 0; r < 16 / NW; ++r) {
-      int key = min(t * BK + 4 * NW * r + st_key, nkeys - 1);
+    for (int r = 0; r < BK / (RPI * NW); ++r) {
+      int key = min(t * BK + RPI * NW * r + st_key, nkeys - 1);
       const bf16_t* src = kbase + (long long)key * D + st_lc * 8;
       // wave-uniform LDS byte address in M0; lane lands at + 16 * lane
-      const unsigned dst = __builtin_amdgcn_readfirstlane(kb + (4 * NW * r + 4 * wave) * ROW_BYTES);
+      const unsigned dst = __builtin_amdgcn_readfirstlane(kb + (RPI * NW * r + RPI * wave) * ROW_BYTES);
       asm volatile("s_mov_b32 m0, %1\n\ts_nop 0\n\tglobal_load_lds_dwordx4 %0, off" : : "v"(src), "s"(dst) : "memory", "m0");
       if (OUT_V) {
         const bf16_t* vsrc = vbase + (long long)key * D + st_lc * 8;
@@ -258,10 +259,11 @@ __global__ void __launch_bounds__(64 * NW) flash_kernel(FlashParams P) {
     const uint4 z = {0u, 0u, 0u, 0u};
 #pragma unroll
     for (int r = 0; r < TILE_BYTES / (16 * 64 * NW); ++r) *reinterpret_cast<uint4*>(x3 + (r * 64 * NW + tid) * 16) = z;
+    static_assert(TILE_BYTES % (16 * 64 * NW) == 0, "the clear covers the slot exactly");
   }
 
   // ---- queries: B operand of S^T = K Q^T, kept in registers -------------------------
-  bf16x8 qreg[QT][8];
+  bf16x8 qreg[QT][KS];
   float sc[QT];
   int qrow[QT];
   bool qvalid[QT];
@@ -272,25 +274,25 @@ __global__ void __launch_bounds__(64 * NW) flash_kernel(FlashParams P) {
     qrow[qt] = qvalid[qt] ? r : P.nq - 1;
     const bf16_t* qp = P.q + (qrow0 + qrow[qt]) * D + 8 * g;
 #pragma unroll
-    for (int ks = 0; ks < 8; ++ks) qreg[qt][ks] = *reinterpret_cast<const bf16x8*>(qp + 16 * ks);
+    for (int ks = 0; ks < KS; ++ks) qreg[qt][ks] = *reinterpret_cast<const bf16x8*>(qp + 16 * ks);
     float c = P.cR ? P.cR[qrow0 + qrow[qt]] : 1.0f;
     c = fmaxf(c, P.cr_min);
     sc[qt] = P.row_scale * LOG2E / c;
   }
 
   // row reads (A of S^T): key row = 32 st + ql, logical chunk 2 ks + g
-  int a_off[8];
+  int a_off[KS];
 #pragma unroll
-  for (int ks = 0; ks < 8; ++ks) a_off[ks] = ql * ROW_BYTES + (((2 * ks + g) ^ swz(ql)) << 4);
+  for (int ks = 0; ks < KS; ++ks) a_off[ks] = ql * ROW_BYTES + (((2 * ks + g) ^ swz(ql)) << 4);
   // transpose reads (A of O^T += X^T P^T): 16-lane group u = lane / 16 -> g = u / 2, channel
   // half u & 1; lane r' of the group supplies key (r' / 4) and channels 4 (r' & 3) .. + 3.
   // For X = V the offsets point into the V slots.
-  int t_off[4][2];
+  int t_off[CT][2];
   {
     const int rp = lane & 15;
     const int chh = (lane >> 4) & 1;
 #pragma unroll
-    for (int ct = 0; ct < 4; ++ct)
+    for (int ct = 0; ct < CT; ++ct)
 #pragma unroll
       for (int hh = 0; hh < 2; ++hh) {
         int key = 8 * hh + 4 * g + (rp >> 2);  // + 32 st + 16 c' added as an immediate
@@ -301,11 +303,11 @@ __global__ void __launch_bounds__(64 * NW) flash_kernel(FlashParams P) {
 
   // ---- accumulators and statistics -------------------------------------------------------
   static_assert(OUT_K != OUT_V, "one accumulator set per pass (see launch_r_update_flash)");
-  f32x16 oacc[QT][4];  // O^T tiles: [query tile][32-channel tile]
+  f32x16 oacc[QT][CT];  // O^T tiles: [query tile][32-channel tile]
 #pragma unroll
   for (int qt = 0; qt < QT; ++qt)
 #pragma unroll
-    for (int ct = 0; ct < 4; ++ct)
+    for (int ct = 0; ct < CT; ++ct)
 #pragma unroll
       for (int r = 0; r < 16; ++r) oacc[qt][ct][r] = 0.f;
   float msc[QT], ltil[QT], hsum[QT];
@@ -334,9 +336,9 @@ __global__ void __launch_bounds__(64 * NW) flash_kernel(FlashParams P) {
 #pragma unroll
       for (int r = 0; r < 16; ++r) sacc[qt][r] = 0.f;
 #pragma unroll
-    for (int ks = 0; ks < 8; ++ks) {
+    for (int ks = 0; ks < KS; ++ks) {
 #ifdef VM_DBG_NO_LDS_S
-      bf16x8 a = qreg[0][(ks + 1) & 7];
+      bf16x8 a = qreg[0][(ks + 1) % KS];
 #else
       bf16x8 a = lds_read_b128(ktile + st * 32 * ROW_BYTES + a_off[ks]);
 #endif
@@ -351,9 +353,9 @@ __global__ void __launch_bounds__(64 * NW) flash_kernel(FlashParams P) {
     for (int c = 0; c < 2; ++c) {
       const int koff = (st * 32 + c * 16) * ROW_BYTES;
 #pragma unroll
-      for (int ct = 0; ct < 4; ++ct) {
+      for (int ct = 0; ct < CT; ++ct) {
 #ifdef VM_DBG_NO_LDS_PV
-        bf16x8 a = qreg[0][(2 * ct + c) & 7];
+        bf16x8 a = qreg[0][(2 * ct + c) % KS];
 #else
         bf16x4 lo = lds_read_tr(ktile + koff + t_off[ct][0]);
         bf16x4 hi = lds_read_tr(ktile + koff + t_off[ct][1]);
@@ -436,7 +438,7 @@ __global__ void __launch_bounds__(64 * NW) flash_kernel(FlashParams P) {
 #pragma unroll
       for (int qt = 0; qt < QT; ++qt)
 #pragma unroll
-        for (int ct = 0; ct < 4; ++ct) scale_acc(oacc[qt][ct], alpha[qt]);
+        for (int ct = 0; ct < CT; ++ct) scale_acc(oacc[qt][ct], alpha[qt]);
     }
   };
 
@@ -493,7 +495,7 @@ __global__ void __launch_bounds__(64 * NW) flash_kernel(FlashParams P) {
   DBG_T(4);
   // ---- epilogue ----------------------------------------------------------------------------
   // Normalised rows are staged in LDS (each wave owns the 32 * QT rows it computed, swizzled
-  // like the key tiles) and leave as whole 256-byte rows, 16 bytes per lane.
+  // like the key tiles) and leave as whole rows, 16 bytes per lane.
   __syncthreads();  // every wave is done with the key/value tiles
   char* stage = smem + wave * (32 * QT * ROW_BYTES);
 #pragma unroll
@@ -513,7 +515,7 @@ __global__ void __launch_bounds__(64 * NW) flash_kernel(FlashParams P) {
         float dot = 0.f;
         const bf16_t* qp = P.q + row * D;
 #pragma unroll
-        for (int ct = 0; ct < 4; ++ct)
+        for (int ct = 0; ct < CT; ++ct)
 #pragma unroll
           for (int c = 0; c < 4; ++c) {
             uint2 w = *reinterpret_cast<const uint2*>(qp + 32 * ct + 8 * c + 4 * g);
@@ -529,7 +531,7 @@ __global__ void __launch_bounds__(64 * NW) flash_kernel(FlashParams P) {
       }
       // lane (q, g) holds channels 32 ct + 8 c + 4 g .. + 3 of query q: 8-byte pieces
 #pragma unroll
-      for (int ct = 0; ct < 4; ++ct)
+      for (int ct = 0; ct < CT; ++ct)
 #pragma unroll
         for (int c = 0; c < 4; ++c) {
           uint2 w;
@@ -544,7 +546,7 @@ __global__ void __launch_bounds__(64 * NW) flash_kernel(FlashParams P) {
         const long long prow = ((long long)split * nprob + prob) * P.nq + qrow[qt];
         if (g == 0) P.part_lse[prow] = lt > 0.f ? msc[qt] + __log2f(lt) : NEG_BIG;
 #pragma unroll
-        for (int ct = 0; ct < 4; ++ct)
+        for (int ct = 0; ct < CT; ++ct)
 #pragma unroll
           for (int c = 0; c < 4; ++c) {
             const int ch = 32 * ct + 8 * c + 4 * g;
@@ -562,9 +564,9 @@ __global__ void __launch_bounds__(64 * NW) flash_kernel(FlashParams P) {
     bf16_t* dst = OUT_K ? P.outk : P.outv;
     const int row_first = qb * BQ + wave * (32 * QT);
 #pragma unroll
-    for (int ps = 0; ps < 8 * QT; ++ps) {
-      const int lr = ps * 4 + (lane >> 4);  // row within the wave's block
-      const int pc = lane & 15;
+    for (int ps = 0; ps < 32 * QT / RPI; ++ps) {
+      const int lr = ps * RPI + lane / CH;  // row within the wave's block
+      const int pc = lane % CH;
       const int lc = pc ^ swz(lr);
       if (row_first + lr < P.nq) {
         uint4 w = *reinterpret_cast<const uint4*>(stage + lr * ROW_BYTES + pc * 16);
@@ -580,6 +582,7 @@ __global__ void __launch_bounds__(128) merge_splits_kernel(const float* __restri
                                                            const float* __restrict__ part_lse, bf16_t* __restrict__ out,
                                                            int nsplit, long long rows_per_split, int nq,
                                                            long long out_rows_per_problem) {
+  const int D = blockDim.x;        // one thread per channel
   const long long r = blockIdx.x;  // problem * nq + row
   const int c = threadIdx.x;       // channel
   const long long prob = r / nq;
@@ -595,18 +598,17 @@ __global__ void __launch_bounds__(128) merge_splits_kernel(const float* __restri
   out[(prob * out_rows_per_problem + row) * D + c] = f32_to_bf16(acc / wsum);
 }
 
-constexpr int FLASH_LDS_BYTES = 2 * NSLOT * TILE_BYTES;  // four K slots + four V slots = 128 KB
-
-template <bool OUT_K, bool OUT_V, int ENT, bool SPLIT>
+template <int D, bool OUT_K, bool OUT_V, int ENT, bool SPLIT>
 hipError_t launch_flash(const FlashParams& P, hipStream_t st) {
-  auto kern = flash_kernel<OUT_K, OUT_V, ENT, SPLIT>;
+  constexpr int LDS_BYTES = 2 * NSLOT * BK * D * 2;  // four K slots + four V slots: 128 KB at d = 128
+  auto kern = flash_kernel<D, OUT_K, OUT_V, ENT, SPLIT>;
   static bool configured = false;  // the attribute is per function, set once per process
   if (!configured) {
-    hipError_t e = hipFuncSetAttribute((const void*)kern, hipFuncAttributeMaxDynamicSharedMemorySize, FLASH_LDS_BYTES);
+    hipError_t e = hipFuncSetAttribute((const void*)kern, hipFuncAttributeMaxDynamicSharedMemorySize, LDS_BYTES);
     if (e != hipSuccess) return e;
     configured = true;
   }
-  hipLaunchKernelGGL(kern, dim3(P.blocks_per_xcd * 8), dim3(64 * NW), FLASH_LDS_BYTES, st, P);
+  hipLaunchKernelGGL(kern, dim3(P.blocks_per_xcd * 8), dim3(64 * NW), LDS_BYTES, st, P);
   return hipGetLastError();
 }
 
@@ -625,7 +627,7 @@ int first_frame_splits(const Dims& dm) {
 
 }  // namespace
 
-bool flash_supported(const Dims& dm) { return dm.d == D; }
+bool flash_supported(const Dims& dm) { return dm.d == 128 || dm.d == 64; }
 #ifdef VM_DBG_TIMING
 extern "C" __attribute__((visibility("default"))) void vmonarch_debug_buffer(void* p) { g_dbg_buf = (unsigned long long*)p; }
 #endif
@@ -654,18 +656,22 @@ hipError_t launch_r_update_flash(const bf16_t* aR, const float* cR, const bf16_t
   // compiles, but the register allocator then spills and serialises every LDS read with its
   // MFMA; measured on the 81 x 28 x 52 workload the whole call took 6.9 ms with it against
   // 6.1 ms with two passes.
-  hipError_t e = ident ? launch_flash<true, false, 2, false>(P, st) : launch_flash<true, false, 1, false>(P, st);
-  if (e != hipSuccess || v == nullptr) return e;
-  P.outk = nullptr;
-  P.cl = nullptr;
-  return launch_flash<false, true, 0, false>(P, st);
+  auto run = [&](auto dc) -> hipError_t {
+    constexpr int D = decltype(dc)::value;
+    hipError_t e = ident ? launch_flash<D, true, false, 2, false>(P, st) : launch_flash<D, true, false, 1, false>(P, st);
+    if (e != hipSuccess || v == nullptr) return e;
+    P.outk = nullptr;
+    P.cl = nullptr;
+    return launch_flash<D, false, true, 0, false>(P, st);
+  };
+  return dm.d == 128 ? run(std::integral_constant<int, 128>{}) : run(std::integral_constant<int, 64>{});
 }
 
 size_t first_frame_flash_scratch_bytes(const Dims& dm) {
   const int ns = first_frame_splits(dm);
   if (ns == 1) return 0;
   size_t rows = (size_t)ns * dm.BH * dm.b;
-  return rows * D * sizeof(float) + ((rows * sizeof(float) + 255) & ~(size_t)255);
+  return rows * dm.d * sizeof(float) + ((rows * sizeof(float) + 255) & ~(size_t)255);
 }
 
 hipError_t launch_first_frame_flash(const bf16_t* q, const bf16_t* k, const bf16_t* v, bf16_t* out, void* scratch,
@@ -687,15 +693,16 @@ hipError_t launch_first_frame_flash(const bf16_t* q, const bf16_t* k, const bf16
   P.blocks_per_xcd = (P.total_blocks + 7) / 8;
   P.row_scale = 1.0f / sqrtf((float)dm.d);
   P.cr_min = 0.f;
-  if (ns == 1) return launch_flash<false, true, 0, false>(P, st);
+  const bool d128 = dm.d == 128;
+  if (ns == 1) return d128 ? launch_flash<128, false, true, 0, false>(P, st) : launch_flash<64, false, true, 0, false>(P, st);
   const size_t rows = (size_t)ns * dm.BH * dm.b;
-  const size_t need = rows * D * sizeof(float) + ((rows * sizeof(float) + 255) & ~(size_t)255);
+  const size_t need = rows * dm.d * sizeof(float) + ((rows * sizeof(float) + 255) & ~(size_t)255);
   if (scratch == nullptr || scratch_bytes < need) return hipErrorInvalidValue;
   P.part_lse = (float*)scratch;
   P.part_o = (float*)((char*)scratch + ((rows * sizeof(float) + 255) & ~(size_t)255));
-  hipError_t e = launch_flash<false, true, 0, true>(P, st);
+  hipError_t e = d128 ? launch_flash<128, false, true, 0, true>(P, st) : launch_flash<64, false, true, 0, true>(P, st);
   if (e != hipSuccess) return e;
-  hipLaunchKernelGGL(merge_splits_kernel, dim3((unsigned)((long long)dm.BH * dm.b)), dim3(D), 0, st, P.part_o,
+  hipLaunchKernelGGL(merge_splits_kernel, dim3((unsigned)((long long)dm.BH * dm.b)), dim3(dm.d), 0, st, P.part_o,
                      P.part_lse, out, ns, (long long)dm.BH * dm.b, dm.b, dm.N);
   return hipGetLastError();
 }

@@ -16,21 +16,15 @@
 //                       alpha_R^T[:, k-tile w] = Q^T L (contraction over all query frames j,
 //                       both operands by LDS transpose reads) and c_R = 1^T L by one extra
 //                       MFMA per step with an all-ones A operand.
-// Results are staged in LDS and leave as whole 256-byte rows.
+// Results are staged in LDS and leave as whole rows.  Instantiated for d = 128 and d = 64.
 #include "common.h"
 
 namespace vm {
 
 namespace {
 
-constexpr int D = 128;
-constexpr int ROW_BYTES = D * 2;
 constexpr float LOG2E = 1.4426950408889634f;
 
-__device__ __forceinline__ int swz(int row) {
-  int x = row & 15;
-  return ((x & 3) << 2) | (x >> 2);
-}
 __device__ __forceinline__ bf16x8 lds_read_b128(const char* p) { return *reinterpret_cast<const bf16x8*>(p); }
 __device__ __forceinline__ bf16x4 lds_read_tr(const char* p) {
   return __builtin_amdgcn_ds_read_tr16_b64_v4bf16(
@@ -46,8 +40,9 @@ __device__ __forceinline__ uint32_t pack_bf16(float a, float b) {
   return u;
 }
 
-template <int NW>
+template <int D, int NW>
 struct Lay {
+  static constexpr int ROW_BYTES = RowGeo<D>::ROW_BYTES;
   static constexpr int TP = 32 * NW;
   static constexpr int TOK = TP * ROW_BYTES;       // one gathered tensor
   static constexpr int LMS = TP * 2 + 16;          // row stride of the bf16 L block
@@ -59,15 +54,22 @@ struct Lay {
   static constexpr int bytes(bool fin) { return 2 * TOK + (fin ? X_BYTES_FINAL : X_BYTES_FIT) + TP * 4; }
 };
 
-template <int NW, bool FINAL>
+template <int D, int NW, bool FINAL>
 __global__ void __launch_bounds__(64 * NW) l_update_mfma_kernel(const bf16_t* __restrict__ q,
                                                                 const bf16_t* __restrict__ aL,
                                                                 const float* __restrict__ cL,
                                                                 const bf16_t* __restrict__ y, bf16_t* __restrict__ aR,
                                                                 float* __restrict__ cR, bf16_t* __restrict__ out, int T,
                                                                 int b, float q_scale) {
-  using LY = Lay<NW>;
+  using LY = Lay<D, NW>;
+  using G = RowGeo<D>;
   constexpr int TP = LY::TP;
+  constexpr int ROW_BYTES = G::ROW_BYTES;
+  constexpr int CH = G::CH;    // 16-byte chunks per row
+  constexpr int KS = G::KS;    // k-steps of a contraction over d
+  constexpr int VT = G::CT;    // 32-channel tiles of a result row
+  constexpr int RPI = G::RPI;  // rows covered by 64 lanes x 16 bytes
+  auto swz = [](int row) { return G::swz(row); };
   extern __shared__ __attribute__((aligned(16))) char smem[];
   char* Qs = smem + LY::OFF_Q;
   char* As = smem + LY::OFF_A;
@@ -84,12 +86,13 @@ __global__ void __launch_bounds__(64 * NW) l_update_mfma_kernel(const bf16_t* __
 
   // ---- gather the position's rows (stride b*d in HBM) into LDS -----------------------
   {
-    const int sub = tid >> 4;        // row within a pass
-    const int pc = tid & 15;         // physical 16-byte chunk
-    uint4 rq[8], ra[8], ry[8];
+    const int sub = tid / CH;        // row within a pass
+    const int pc = tid % CH;         // physical 16-byte chunk
+    constexpr int NPS = 32 / RPI;    // passes: RPI * NW rows each
+    uint4 rq[NPS], ra[NPS], ry[NPS];
 #pragma unroll
-    for (int ps = 0; ps < 8; ++ps) {
-      const int row = ps * 4 * NW + sub;
+    for (int ps = 0; ps < NPS; ++ps) {
+      const int row = ps * RPI * NW + sub;
       const int lc = pc ^ swz(row);
       uint4 z = {0u, 0u, 0u, 0u};
       rq[ps] = z; ra[ps] = z;
@@ -103,8 +106,8 @@ __global__ void __launch_bounds__(64 * NW) l_update_mfma_kernel(const bf16_t* __
     }
     for (int kk = tid; kk < TP; kk += 64 * NW) sCL[kk] = kk < T ? cL[head0 + (long long)kk * b + i] * LOG2E : 0.f;
 #pragma unroll
-    for (int ps = 0; ps < 8; ++ps) {
-      const int row = ps * 4 * NW + sub;
+    for (int ps = 0; ps < NPS; ++ps) {
+      const int row = ps * RPI * NW + sub;
       *reinterpret_cast<uint4*>(Qs + row * ROW_BYTES + pc * 16) = rq[ps];
       *reinterpret_cast<uint4*>(As + row * ROW_BYTES + pc * 16) = ra[ps];
       if (FINAL) *reinterpret_cast<uint4*>(Xs + row * ROW_BYTES + pc * 16) = ry[ps];
@@ -114,9 +117,9 @@ __global__ void __launch_bounds__(64 * NW) l_update_mfma_kernel(const bf16_t* __
 
   // ---- U^T = aL Q^T for the wave's 32 query frames -------------------------------------
   const int jrow = 32 * wave + ql;  // query frame of this lane
-  bf16x8 qreg[8];
+  bf16x8 qreg[KS];
 #pragma unroll
-  for (int ks = 0; ks < 8; ++ks)
+  for (int ks = 0; ks < KS; ++ks)
     qreg[ks] = lds_read_b128(Qs + jrow * ROW_BYTES + (((2 * ks + g) ^ swz(ql)) << 4));
   f32x16 u[NW];
 #pragma unroll
@@ -124,7 +127,7 @@ __global__ void __launch_bounds__(64 * NW) l_update_mfma_kernel(const bf16_t* __
 #pragma unroll
     for (int r = 0; r < 16; ++r) u[kt][r] = 0.f;
 #pragma unroll
-    for (int ks = 0; ks < 8; ++ks) {
+    for (int ks = 0; ks < KS; ++ks) {
       bf16x8 a = lds_read_b128(As + (32 * kt + ql) * ROW_BYTES + (((2 * ks + g) ^ swz(ql)) << 4));
       u[kt] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(a, qreg[ks], u[kt], 0, 0, 0);
     }
@@ -164,9 +167,9 @@ __global__ void __launch_bounds__(64 * NW) l_update_mfma_kernel(const bf16_t* __
   // transpose-read geometry shared by both second contractions
   const int rp = lane & 15;
   const int chh = (lane >> 4) & 1;
-  f32x16 acc[4];
+  f32x16 acc[VT];
 #pragma unroll
-  for (int vt = 0; vt < 4; ++vt)
+  for (int vt = 0; vt < VT; ++vt)
 #pragma unroll
     for (int r = 0; r < 16; ++r) acc[vt][r] = 0.f;
 
@@ -195,7 +198,7 @@ __global__ void __launch_bounds__(64 * NW) l_update_mfma_kernel(const bf16_t* __
         bf16x8 pb;
         __builtin_memcpy(&pb, w, 16);
 #pragma unroll
-        for (int vt = 0; vt < 4; ++vt) {
+        for (int vt = 0; vt < VT; ++vt) {
           bf16x4 part[2];
 #pragma unroll
           for (int hh = 0; hh < 2; ++hh) {
@@ -210,7 +213,7 @@ __global__ void __launch_bounds__(64 * NW) l_update_mfma_kernel(const bf16_t* __
     sumt += __shfl_xor(sumt, 32);
     const float invt = 1.0f / sumt;
 #pragma unroll
-    for (int vt = 0; vt < 4; ++vt)
+    for (int vt = 0; vt < VT; ++vt)
 #pragma unroll
       for (int r = 0; r < 16; ++r) acc[vt][r] *= invt;
     Os = Qs;  // rows 32w..32w+31 of Qs are read by this wave only, and it is done with them
@@ -245,7 +248,7 @@ __global__ void __launch_bounds__(64 * NW) l_update_mfma_kernel(const bf16_t* __
       }
       bf16x8 bL = __builtin_shufflevector(lpart[0], lpart[1], 0, 1, 2, 3, 4, 5, 6, 7);
 #pragma unroll
-      for (int vt = 0; vt < 4; ++vt) {
+      for (int vt = 0; vt < VT; ++vt) {
         bf16x4 part[2];
 #pragma unroll
         for (int hh = 0; hh < 2; ++hh) {
@@ -264,7 +267,7 @@ __global__ void __launch_bounds__(64 * NW) l_update_mfma_kernel(const bf16_t* __
 
   // ---- stage the wave's 32 result rows and write them out as whole rows ---------------------
 #pragma unroll
-  for (int vt = 0; vt < 4; ++vt)
+  for (int vt = 0; vt < VT; ++vt)
 #pragma unroll
     for (int c = 0; c < 4; ++c) {
       uint2 w;
@@ -275,9 +278,9 @@ __global__ void __launch_bounds__(64 * NW) l_update_mfma_kernel(const bf16_t* __
   __syncthreads();
   bf16_t* dst = FINAL ? out : aR;
 #pragma unroll
-  for (int ps = 0; ps < 8; ++ps) {
-    const int row = 32 * wave + ps * 4 + (lane >> 4);
-    const int pc = lane & 15;
+  for (int ps = 0; ps < 32 / RPI; ++ps) {
+    const int row = 32 * wave + ps * RPI + lane / CH;
+    const int pc = lane % CH;
     const int lc = pc ^ swz(row);
     if (row < T) {
       uint4 w = *reinterpret_cast<const uint4*>(Os + row * ROW_BYTES + pc * 16);
@@ -286,11 +289,11 @@ __global__ void __launch_bounds__(64 * NW) l_update_mfma_kernel(const bf16_t* __
   }
 }
 
-template <int NW, bool FINAL>
+template <int D, int NW, bool FINAL>
 hipError_t launch_nw(const bf16_t* q, const bf16_t* aL, const float* cL, const bf16_t* y, bf16_t* aR, float* cR,
                      bf16_t* out, const Dims& dm, float q_scale, hipStream_t st) {
-  auto kern = l_update_mfma_kernel<NW, FINAL>;
-  const int lds = Lay<NW>::bytes(FINAL);
+  auto kern = l_update_mfma_kernel<D, NW, FINAL>;
+  const int lds = Lay<D, NW>::bytes(FINAL);
   if (lds > 48 * 1024) {
     hipError_t e = hipFuncSetAttribute((const void*)kern, hipFuncAttributeMaxDynamicSharedMemorySize, lds);
     if (e != hipSuccess) return e;
@@ -299,27 +302,31 @@ hipError_t launch_nw(const bf16_t* q, const bf16_t* aL, const float* cL, const b
   return hipGetLastError();
 }
 
-template <bool FINAL>
+template <int D, bool FINAL>
 hipError_t launch_fin(const bf16_t* q, const bf16_t* aL, const float* cL, const bf16_t* y, bf16_t* aR, float* cR,
                       bf16_t* out, const Dims& dm, float q_scale, hipStream_t st) {
   const int nw = (dm.T + 31) / 32;
   switch (nw) {
-    case 1: return launch_nw<1, FINAL>(q, aL, cL, y, aR, cR, out, dm, q_scale, st);
-    case 2: return launch_nw<2, FINAL>(q, aL, cL, y, aR, cR, out, dm, q_scale, st);
-    case 3: return launch_nw<3, FINAL>(q, aL, cL, y, aR, cR, out, dm, q_scale, st);
-    case 4: return launch_nw<4, FINAL>(q, aL, cL, y, aR, cR, out, dm, q_scale, st);
+    case 1: return launch_nw<D, 1, FINAL>(q, aL, cL, y, aR, cR, out, dm, q_scale, st);
+    case 2: return launch_nw<D, 2, FINAL>(q, aL, cL, y, aR, cR, out, dm, q_scale, st);
+    case 3: return launch_nw<D, 3, FINAL>(q, aL, cL, y, aR, cR, out, dm, q_scale, st);
+    case 4: return launch_nw<D, 4, FINAL>(q, aL, cL, y, aR, cR, out, dm, q_scale, st);
     default: return hipErrorInvalidValue;
   }
 }
 
 }  // namespace
 
-bool lpass_supported(const Dims& dm) { return dm.d == D && dm.T <= 128; }
+bool lpass_supported(const Dims& dm) { return (dm.d == 128 || dm.d == 64) && dm.T <= 128; }
 
 hipError_t launch_l_update_mfma(const bf16_t* q, const bf16_t* aL, const float* cL, const bf16_t* y, bf16_t* aR,
                                 float* cR, bf16_t* out, const Dims& dm, float q_scale, hipStream_t st) {
-  if (y != nullptr) return launch_fin<true>(q, aL, cL, y, aR, cR, out, dm, q_scale, st);
-  return launch_fin<false>(q, aL, cL, y, aR, cR, out, dm, q_scale, st);
+  if (dm.d == 128) {
+    if (y != nullptr) return launch_fin<128, true>(q, aL, cL, y, aR, cR, out, dm, q_scale, st);
+    return launch_fin<128, false>(q, aL, cL, y, aR, cR, out, dm, q_scale, st);
+  }
+  if (y != nullptr) return launch_fin<64, true>(q, aL, cL, y, aR, cR, out, dm, q_scale, st);
+  return launch_fin<64, false>(q, aL, cL, y, aR, cR, out, dm, q_scale, st);
 }
 
 }  // namespace vm
