@@ -62,6 +62,12 @@ WORKLOADS = {
     "long-81x28x52": Workload("long-81x28x52", 3, 1, 12, 81, 28, 52, 128, "bf16", 2, True),
     "stress-1m": Workload("stress-1m", 4, 1, 12, 81, 90, 136, 128, "bf16", 1, False),
 }
+# The paper's own kernel benchmark (App. "Kernel Optimization of VMonarch"): batch 1, 12 heads,
+# d = 64, 2 sweeps, m = 32 blocks of b = N / 32 tokens, N = 2^10 .. 2^16; no video shape, no
+# recomputation.  Expressed here as T = m, Hs = 1, Ws = b.
+for _lg in range(10, 17):
+    _n = f"kernel-bench-{1 << (_lg - 10)}k"
+    WORKLOADS[_n] = Workload(_n, 10 + _lg, 1, 12, 32, 1, (1 << _lg) // 32, 64, "bf16", 2, False)
 
 
 def f32_to_bf16_bits(x: np.ndarray) -> np.ndarray:

@@ -64,6 +64,12 @@ def test_million_token_stress_single_head(env):
     _run_workload(env, "stress-1m", [5], 8, 4)
 
 
+def test_paper_kernel_benchmark_shape_sampled_positions(env):
+    """d = 64, m = 32 blocks of b = 2048 tokens (N = 2^16), 2 sweeps: the largest shape of the
+    paper's own kernel benchmark; 2 of the 12 heads."""
+    _run_workload(env, "kernel-bench-64k", [0, 11], 24, 5)
+
+
 def test_headline_long_video_sampled_positions_and_invariants(env):
     torch, binding, dev = env
     tq, tk, tv, out, wl = _run_workload(env, "long-81x28x52", [0, 5, 11], 24, 2)
