@@ -42,15 +42,6 @@ constexpr float LOG2E = 1.4426950408889634f;
 constexpr float LN2 = 0.6931471805599453f;
 constexpr float RESCALE_TH = 8.0f;  // rescale the accumulators only when a row max grows by 2^8
 constexpr float NEG_BIG = -1.0e30f;
-#ifndef VM_SCHED_GROUPS
-#define VM_SCHED_GROUPS 0
-#endif
-#ifndef VM_SCHED_VALU
-#define VM_SCHED_VALU 4
-#endif
-#ifndef VM_SCHED_HEAD
-#define VM_SCHED_HEAD 16
-#endif
 
 struct FlashParams {
   const bf16_t* q;      // query rows
@@ -73,16 +64,7 @@ struct FlashParams {
   int blocks_per_xcd;   // ceil(total_blocks / 8)
   float row_scale;
   float cr_min;
-#ifdef VM_DBG_TIMING
-  unsigned long long* dbg;
-#endif
 };
-#ifdef VM_DBG_TIMING
-unsigned long long* g_dbg_buf = nullptr;
-#define DBG_T(slot) do { if (dbg_on) { unsigned long long tt = __builtin_amdgcn_s_memtime(); P.dbg[(wave >> 2) * 512 + (slot)] = tt; } } while (0)
-#else
-#define DBG_T(slot) do { } while (0)
-#endif
 
 __device__ __forceinline__ bf16x8 lds_read_b128(const char* p) { return *reinterpret_cast<const bf16x8*>(p); }
 
@@ -148,11 +130,7 @@ __device__ __forceinline__ void subtile_probs(const f32x16& s, float sc, float m
 #pragma unroll
   for (int r = 0; r < 16; ++r) {
     float t = __builtin_fmaf(s[r], sc, -msc);
-#ifdef VM_DBG_NO_EXP
-    p[r] = t * 1.0e-3f;
-#else
     p[r] = __builtin_amdgcn_exp2f(t);
-#endif
     if (ENT == 1) h = __builtin_fmaf(p[r], t, h);
   }
 #pragma unroll
@@ -201,10 +179,6 @@ __global__ void __launch_bounds__(64 * NW) flash_kernel(FlashParams P) {
   const int ql = lane & 31;
   const int g = lane >> 5;
 
-#ifdef VM_DBG_TIMING
-  const bool dbg_on = (wid == P.total_blocks / 2) && ((wave & 3) == 0) && lane == 0 && P.dbg != nullptr;
-#endif
-  DBG_T(0);
   const int kbeg = split * P.keys_per_split;
   const int kend = min(P.nk, kbeg + P.keys_per_split);
   const int nkeys = kend - kbeg;
@@ -337,11 +311,7 @@ __global__ void __launch_bounds__(64 * NW) flash_kernel(FlashParams P) {
       for (int r = 0; r < 16; ++r) sacc[qt][r] = 0.f;
 #pragma unroll
     for (int ks = 0; ks < KS; ++ks) {
-#ifdef VM_DBG_NO_LDS_S
-      bf16x8 a = qreg[0][(ks + 1) % KS];
-#else
       bf16x8 a = lds_read_b128(ktile + st * 32 * ROW_BYTES + a_off[ks]);
-#endif
 #pragma unroll
       for (int qt = 0; qt < QT; ++qt)
         sacc[qt] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(a, qreg[qt][ks], sacc[qt], 0, 0, 0);
@@ -354,13 +324,9 @@ __global__ void __launch_bounds__(64 * NW) flash_kernel(FlashParams P) {
       const int koff = (st * 32 + c * 16) * ROW_BYTES;
 #pragma unroll
       for (int ct = 0; ct < CT; ++ct) {
-#ifdef VM_DBG_NO_LDS_PV
-        bf16x8 a = qreg[0][(2 * ct + c) % KS];
-#else
         bf16x4 lo = lds_read_tr(ktile + koff + t_off[ct][0]);
         bf16x4 hi = lds_read_tr(ktile + koff + t_off[ct][1]);
         bf16x8 a = __builtin_shufflevector(lo, hi, 0, 1, 2, 3, 4, 5, 6, 7);
-#endif
 #pragma unroll
         for (int qt = 0; qt < QT; ++qt)
           oacc[qt][ct] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(a, pb[qt][c], oacc[qt][ct], 0, 0, 0);
@@ -416,24 +382,6 @@ __global__ void __launch_bounds__(64 * NW) flash_kernel(FlashParams P) {
       asm volatile("" : "+v"(pbcur[qt][0]), "+v"(pbcur[qt][1]), "+v"(ltil[qt]), "+v"(mpend[qt]));
       if (ENT == 1) asm volatile("" : "+v"(hsum[qt]));
     }
-#if VM_SCHED_GROUPS == 2
-    // Issue order handed to the scheduler: the LDS reads of the first MFMA group, a slice of
-    // vector work while they are in flight, the first group one MFMA at a time with the
-    // reads of the second group and more vector work beside it, then the second group.
-    __builtin_amdgcn_sched_group_barrier(0x100, 8, 0);
-    __builtin_amdgcn_sched_group_barrier(0x002, VM_SCHED_HEAD, 0);
-#pragma unroll
-    for (int i = 0; i < 8; ++i) {
-      __builtin_amdgcn_sched_group_barrier(0x008, 1, 0);
-      __builtin_amdgcn_sched_group_barrier(0x100, 2, 0);
-      __builtin_amdgcn_sched_group_barrier(0x002, VM_SCHED_VALU, 0);
-    }
-#pragma unroll
-    for (int i = 0; i < 8; ++i) {
-      __builtin_amdgcn_sched_group_barrier(0x008, 1, 0);
-      __builtin_amdgcn_sched_group_barrier(0x002, VM_SCHED_VALU, 0);
-    }
-#endif
     if (moved_now) {
 #pragma unroll
       for (int qt = 0; qt < QT; ++qt)
@@ -441,8 +389,6 @@ __global__ void __launch_bounds__(64 * NW) flash_kernel(FlashParams P) {
         for (int ct = 0; ct < CT; ++ct) scale_acc(oacc[qt][ct], alpha[qt]);
     }
   };
-
-  DBG_T(1);
   if (ntiles > 0) {
     // Four LDS slots, tile t in slot t & 3: during tile t the products of the last sub-tile of
     // tile t-1 are still outstanding, tile t+1 is resident (its first sub-tile is needed one
@@ -460,26 +406,21 @@ __global__ void __launch_bounds__(64 * NW) flash_kernel(FlashParams P) {
     }
     logits(smem, 0, sA);
     look_ahead(sA);
-    DBG_T(2);
     const int last_left = nkeys - (ntiles - 1) * BK;  // 1..64 keys in the last tile
     // Four tiles per trip so that every LDS slot offset is an instruction immediate (tile t
     // sits in slot t & 3 and a trip starts at a multiple of four).
     auto tile_iteration = [&](auto slot_c, int t) {
       constexpr int SLOT = decltype(slot_c)::value;
-      DBG_T(8 + 4 * t);
       if (t > 0) {
         asm volatile("s_waitcnt vmcnt(0)" ::: "memory");
-        DBG_T(9 + 4 * t);
         __syncthreads();  // tile t+1 has landed for everyone; everyone is done with tile t-2
       }
-      DBG_T(10 + 4 * t);
       if (t + 2 < ntiles) issue_tile(t + 2);
       const char* kp = smem + ((SLOT + 3) & 3) * TILE_BYTES;  // tile t-1
       const char* kt = smem + SLOT * TILE_BYTES;
       const char* kn = smem + ((SLOT + 1) & 3) * TILE_BYTES;
       const int left0 = t == ntiles - 1 ? last_left : 64;
       step(sA, sB, pbB, pbA, kt, 1, kp, 1, left0);  // at t = 0: P^T = 0 against the cleared slot 3
-      DBG_T(11 + 4 * t);
       step(sB, sA, pbA, pbB, kn, 0, kt, 0, left0 - 32);
     };
     for (int t0 = 0; t0 < ntiles; t0 += 4) {
@@ -488,11 +429,8 @@ __global__ void __launch_bounds__(64 * NW) flash_kernel(FlashParams P) {
       if (t0 + 2 < ntiles) tile_iteration(std::integral_constant<int, 2>{}, t0 + 2);
       if (t0 + 3 < ntiles) tile_iteration(std::integral_constant<int, 3>{}, t0 + 3);
     }
-    DBG_T(3);
     accumulate(smem + ((ntiles - 1) & 3) * TILE_BYTES, 1, pbB);  // drain: the products of the last sub-tile
   }
-
-  DBG_T(4);
   // ---- epilogue ----------------------------------------------------------------------------
   // Normalised rows are staged in LDS (each wave owns the 32 * QT rows it computed, swizzled
   // like the key tiles) and leave as whole rows, 16 bytes per lane.
@@ -574,7 +512,6 @@ __global__ void __launch_bounds__(64 * NW) flash_kernel(FlashParams P) {
       }
     }
   }
-  DBG_T(5);
 }
 
 // Merge of the key-range partials of the first-frame recomputation: weights 2^(lse - max).
@@ -628,9 +565,6 @@ int first_frame_splits(const Dims& dm) {
 }  // namespace
 
 bool flash_supported(const Dims& dm) { return dm.d == 128 || dm.d == 64; }
-#ifdef VM_DBG_TIMING
-extern "C" __attribute__((visibility("default"))) void vmonarch_debug_buffer(void* p) { g_dbg_buf = (unsigned long long*)p; }
-#endif
 
 hipError_t launch_r_update_flash(const bf16_t* aR, const float* cR, const bf16_t* k, const bf16_t* v, bf16_t* aL,
                                  float* cL, bf16_t* y, const Dims& dm, float row_scale, float cr_min, int entropy_mode,
@@ -647,9 +581,6 @@ hipError_t launch_r_update_flash(const bf16_t* aR, const float* cR, const bf16_t
   P.total_blocks = (int)total;
   P.blocks_per_xcd = (P.total_blocks + 7) / 8;
   P.row_scale = row_scale; P.cr_min = cr_min;
-#ifdef VM_DBG_TIMING
-  P.dbg = g_dbg_buf;
-#endif
   const bool ident = entropy_mode == VMONARCH_ENTROPY_IDENTITY;
   // alpha_L and c_L from one pass over K; y = R V from a second pass that recomputes the
   // logits.  The single-pass variant (flash_kernel<true, true, ...>, both accumulator sets)
