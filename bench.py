@@ -80,6 +80,45 @@ def recorded_traffic():
     return None
 
 
+def sweep_frames(args) -> int:
+    """Context for the paper's speed-versus-length figure (Sec. 4.3): spatial size 28 x 52, T = 20 .. 48
+    latent frames, 12 heads, d = 128, 2 sweeps + first-frame recomputation, against exact dense
+    attention over the same tokens computed by this library's own blocked-softmax kernel (one
+    "frame" holding all N tokens).  One JSON line per T."""
+    import torch
+
+    from paper_2601_22275_amd import binding, synth
+
+    dev = torch.device("cuda:0")
+    binding.lib()
+    heads, Hs, Ws, d = 12, 28, 52, 128
+    for T in range(20, 49, 4):
+        wl = synth.Workload(f"sweep-{T}x28x52", 20 + T, 1, heads, T, Hs, Ws, d, "bf16", 2, True)
+        q, k, v = synth.make_inputs(wl)
+        tq, tk, tv = (torch.from_numpy(x).to(dev).view(torch.bfloat16).view(1, heads, wl.N, d) for x in (q, k, v))
+        out = torch.empty_like(tq)
+
+        def timed(f):
+            for _ in range(args.warmup):
+                f()
+            torch.cuda.synchronize()
+            e0, e1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+            e0.record()
+            for _ in range(args.steps):
+                f()
+            e1.record()
+            torch.cuda.synchronize()
+            return e0.elapsed_time(e1) / args.steps
+
+        ms_monarch = timed(lambda: binding.attention(tq, tk, tv, T, Hs, Ws, 2, True, out=out))
+        ms_dense = timed(lambda: binding.first_frame_attention(tq, tk, tv, 1, 1, wl.N, out))
+        fl = synth.algorithmic_flops(1, heads, T, wl.b, d, 2, True)
+        print(json.dumps({"T": T, "N": wl.N, "monarch_ms": ms_monarch, "dense_ms": ms_dense,
+                          "dense_over_monarch": ms_dense / ms_monarch, "monarch_tflops": fl / ms_monarch / 1e9,
+                          "dense_tflops": 4.0 * heads * wl.N * wl.N * d / ms_dense / 1e9}), flush=True)
+    return 0
+
+
 def main() -> int:
     ap = argparse.ArgumentParser()
     ap.add_argument("--gpus", type=int, default=1)
@@ -90,6 +129,8 @@ def main() -> int:
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--copy-calibration", action="store_true",
                     help="also run one token-permutation copy of known size (reference for HBM byte counters)")
+    ap.add_argument("--sweep-frames", action="store_true",
+                    help="time T = 20..48 frames of 28x52 tokens against exact dense attention instead of the benchmark")
     args = ap.parse_args()
     if args.gpus != 1:
         print("bench.py: this build runs on ONE GPU only (no sharding, no collectives); use --gpus 1", file=sys.stderr)
@@ -103,6 +144,8 @@ def main() -> int:
     if not torch.cuda.is_available():
         print("bench.py: no GPU visible", file=sys.stderr)
         return 2
+    if args.sweep_frames:
+        return sweep_frames(args)
     binding.lib()  # fail loudly when the HIP library is missing
     wl = synth.WORKLOADS[args.workload]
     dev = torch.device("cuda:0")
