@@ -113,6 +113,21 @@ int vmonarch_r_update_f32(const void* aR, const float* cR, const void* k, const 
                           int Ws, int d, float row_scale, float cr_min, void* stream);
 
 /*
+ * The same R-update, which also returns the log-sum-exp of every query row's logits, the
+ * per-row statistic Alg. 1 hands to the backward pass (Alg. 2) beside the entropy:
+ *     lse_out[k,i] = log sum_l exp z[l]        (natural log; float32 [B][heads][T][b])
+ * The row entropy of Alg. 1 is H = -cL_out.  On the bf16 MFMA path the sum inside the
+ * logarithm is taken over the bf16-rounded probabilities (absolute error about 1e-3).
+ * lse_out must not be NULL.
+ */
+int vmonarch_r_update_lse(const void* aR, const float* cR, const void* k, const void* v, void* aL_out,
+                          float* cL_out, void* y_out, float* lse_out, int B, int heads, int T, int Hs,
+                          int Ws, int d, float row_scale, float cr_min, void* stream);
+int vmonarch_r_update_lse_f32(const void* aR, const float* cR, const void* k, const void* v,
+                              void* aL_out, float* cL_out, void* y_out, float* lse_out, int B, int heads,
+                              int T, int Hs, int Ws, int d, float row_scale, float cr_min, void* stream);
+
+/*
  * L-update, the inter-frame (temporal) factor (Eq. L with Eq. alpha_R/c_R; App. A
  * L_update), walking the frame-major tensors with stride b*d (the permutation P of
  * Sec. 3.1 is applied as addressing, never as a copy).  For every position i:
@@ -140,6 +155,18 @@ int vmonarch_first_frame_attention(const void* q, const void* k, const void* v, 
                                    int heads, int T, int Hs, int Ws, int d, void* stream);
 int vmonarch_first_frame_attention_f32(const void* q, const void* k, const void* v, void* out,
                                        int B, int heads, int T, int Hs, int Ws, int d, void* stream);
+
+/*
+ * The same recomputation, which also returns lse_out[0:b] = log sum_n exp(Q[i] . K[n] / sqrt(d))
+ * over all N keys (natural log).  lse_out: float32 [B][heads][T][b] like every per-token scalar;
+ * only the entries of frame 0 are written.  lse_out must not be NULL.
+ */
+int vmonarch_first_frame_attention_lse(const void* q, const void* k, const void* v, void* out,
+                                       float* lse_out, int B, int heads, int T, int Hs, int Ws, int d,
+                                       void* stream);
+int vmonarch_first_frame_attention_lse_f32(const void* q, const void* k, const void* v, void* out,
+                                           float* lse_out, int B, int heads, int T, int Hs, int Ws,
+                                           int d, void* stream);
 
 /*
  * Permutation P_(b,N) of Sec. 3.1 (its footnote: reshape to m x b, transpose, flatten).

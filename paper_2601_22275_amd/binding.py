@@ -28,6 +28,8 @@ EXPORTS = [
     "vmonarch_r_update", "vmonarch_r_update_f32", "vmonarch_l_update", "vmonarch_l_update_f32",
     "vmonarch_first_frame_attention", "vmonarch_first_frame_attention_f32", "vmonarch_index_maps",
     "vmonarch_permute_tokens", "vmonarch_set_phase_timing", "vmonarch_get_phase_timing",
+    "vmonarch_r_update_lse", "vmonarch_r_update_lse_f32", "vmonarch_first_frame_attention_lse",
+    "vmonarch_first_frame_attention_lse_f32",
 ]
 
 
@@ -61,6 +63,10 @@ def lib() -> ctypes.CDLL:
             getattr(L, name).argtypes = [c_void_p] * 4 + dims + [c_int, c_int, c_void_p]
         for name in ("vmonarch_r_update", "vmonarch_r_update_f32"):
             getattr(L, name).argtypes = [c_void_p] * 7 + dims + [c_float, c_float, c_void_p]
+        for name in ("vmonarch_r_update_lse", "vmonarch_r_update_lse_f32"):
+            getattr(L, name).argtypes = [c_void_p] * 8 + dims + [c_float, c_float, c_void_p]
+        for name in ("vmonarch_first_frame_attention_lse", "vmonarch_first_frame_attention_lse_f32"):
+            getattr(L, name).argtypes = [c_void_p] * 5 + dims + [c_void_p]
         for name in ("vmonarch_l_update", "vmonarch_l_update_f32"):
             getattr(L, name).argtypes = [c_void_p] * 7 + dims + [c_float, c_void_p]
         for name in ("vmonarch_first_frame_attention", "vmonarch_first_frame_attention_f32"):
@@ -165,6 +171,19 @@ def r_update(aR, cR, k, v, T, Hs, Ws, row_scale, cr_min):
     return aL, cL, y
 
 
+def r_update_lse(aR, cR, k, v, T, Hs, Ws, row_scale, cr_min):
+    """Like r_update; returns (aL, cL, y or None, lse) with lse [B, heads, T*b] float32."""
+    B, heads, N, d = aR.shape
+    aL = torch.empty_like(aR)
+    cL = torch.empty((B, heads, N), dtype=torch.float32, device=aR.device)
+    lse = torch.empty((B, heads, N), dtype=torch.float32, device=aR.device)
+    y = torch.empty_like(aR) if v is not None else None
+    fn = getattr(lib(), "vmonarch_r_update_lse" + _suffix(aR))
+    _check(fn(_ptr(aR), _ptr(cR), _ptr(k), _ptr(v), _ptr(aL), _ptr(cL), _ptr(y), _ptr(lse), B, heads, T, Hs, Ws, d,
+              c_float(row_scale), c_float(cr_min), _stream()))
+    return aL, cL, y, lse
+
+
 def l_update(q, aL, cL, y, T, Hs, Ws, q_scale):
     """Fitting sweep (y None): returns (aR, cR).  Last sweep (y given): returns out."""
     B, heads, N, d = q.shape
@@ -187,6 +206,15 @@ def first_frame_attention(q, k, v, T, Hs, Ws, out):
     fn = getattr(lib(), "vmonarch_first_frame_attention" + _suffix(q))
     _check(fn(_ptr(q), _ptr(k), _ptr(v), _ptr(out), B, heads, T, Hs, Ws, d, _stream()))
     return out
+
+
+def first_frame_attention_lse(q, k, v, T, Hs, Ws, out):
+    """Like first_frame_attention; also returns lse [B, heads, T*b] float32 (frame-0 entries written)."""
+    B, heads, N, d = q.shape
+    lse = torch.zeros((B, heads, N), dtype=torch.float32, device=q.device)
+    fn = getattr(lib(), "vmonarch_first_frame_attention_lse" + _suffix(q))
+    _check(fn(_ptr(q), _ptr(k), _ptr(v), _ptr(out), _ptr(lse), B, heads, T, Hs, Ws, d, _stream()))
+    return out, lse
 
 
 def index_maps(T, Hs, Ws):

@@ -140,22 +140,22 @@ void* get_workspace(size_t bytes, int* err) {
 }
 
 template <typename E>
-int r_update_any(const E* aR, const float* cR, const E* k, const E* v, E* aL, float* cL, E* y, const Dims& dm,
-                 float row_scale, float cr_min, hipStream_t st);
+int r_update_any(const E* aR, const float* cR, const E* k, const E* v, E* aL, float* cL, E* y, float* lse,
+                 const Dims& dm, float row_scale, float cr_min, hipStream_t st);
 template <>
 int r_update_any<float>(const float* aR, const float* cR, const float* k, const float* v, float* aL, float* cL,
-                        float* y, const Dims& dm, float row_scale, float cr_min, hipStream_t st) {
-  hipError_t e = launch_r_update_generic<float>(aR, cR, k, v, aL, cL, y, dm, row_scale, cr_min, st);
+                        float* y, float* lse, const Dims& dm, float row_scale, float cr_min, hipStream_t st) {
+  hipError_t e = launch_r_update_generic<float>(aR, cR, k, v, aL, cL, y, lse, dm, row_scale, cr_min, st);
   return e == hipSuccess ? VMONARCH_OK : hip_fail(e, "r_update (plain-ALU f32) launch");
 }
 template <>
 int r_update_any<bf16_t>(const bf16_t* aR, const float* cR, const bf16_t* k, const bf16_t* v, bf16_t* aL, float* cL,
-                         bf16_t* y, const Dims& dm, float row_scale, float cr_min, hipStream_t st) {
+                         bf16_t* y, float* lse, const Dims& dm, float row_scale, float cr_min, hipStream_t st) {
   hipError_t e;
   if (flash_supported(dm))
-    e = launch_r_update_flash(aR, cR, k, v, aL, cL, y, dm, row_scale, cr_min, g_entropy_mode, st);
+    e = launch_r_update_flash(aR, cR, k, v, aL, cL, y, lse, dm, row_scale, cr_min, g_entropy_mode, st);
   else
-    e = launch_r_update_generic<bf16_t>(aR, cR, k, v, aL, cL, y, dm, row_scale, cr_min, st);
+    e = launch_r_update_generic<bf16_t>(aR, cR, k, v, aL, cL, y, lse, dm, row_scale, cr_min, st);
   return e == hipSuccess ? VMONARCH_OK : hip_fail(e, "r_update (bf16) launch");
 }
 
@@ -184,22 +184,22 @@ int l_update_any<bf16_t>(const bf16_t* q, const bf16_t* aL, const float* cL, con
 }
 
 template <typename E>
-int first_frame_any(const E* q, const E* k, const E* v, E* out, void* scratch, size_t scratch_bytes, const Dims& dm,
-                    hipStream_t st);
+int first_frame_any(const E* q, const E* k, const E* v, E* out, float* lse, void* scratch, size_t scratch_bytes,
+                    const Dims& dm, hipStream_t st);
 template <>
-int first_frame_any<float>(const float* q, const float* k, const float* v, float* out, void*, size_t, const Dims& dm,
-                           hipStream_t st) {
-  hipError_t e = launch_first_frame_generic<float>(q, k, v, out, dm, st);
+int first_frame_any<float>(const float* q, const float* k, const float* v, float* out, float* lse, void*, size_t,
+                           const Dims& dm, hipStream_t st) {
+  hipError_t e = launch_first_frame_generic<float>(q, k, v, out, lse, dm, st);
   return e == hipSuccess ? VMONARCH_OK : hip_fail(e, "first_frame (plain-ALU f32) launch");
 }
 template <>
-int first_frame_any<bf16_t>(const bf16_t* q, const bf16_t* k, const bf16_t* v, bf16_t* out, void* scratch,
+int first_frame_any<bf16_t>(const bf16_t* q, const bf16_t* k, const bf16_t* v, bf16_t* out, float* lse, void* scratch,
                             size_t scratch_bytes, const Dims& dm, hipStream_t st) {
   hipError_t e;
   if (flash_supported(dm))
-    e = launch_first_frame_flash(q, k, v, out, scratch, scratch_bytes, dm, st);
+    e = launch_first_frame_flash(q, k, v, out, lse, scratch, scratch_bytes, dm, st);
   else
-    e = launch_first_frame_generic<bf16_t>(q, k, v, out, dm, st);
+    e = launch_first_frame_generic<bf16_t>(q, k, v, out, lse, dm, st);
   return e == hipSuccess ? VMONARCH_OK : hip_fail(e, "first_frame (bf16) launch");
 }
 
@@ -234,7 +234,7 @@ int attention_impl(const void* q_, const void* k_, const void* v_, void* out_, i
     const bool last = sweep == iters - 1;
     phase_mark(st, last ? "r_update_last" : "r_update");
     rc = r_update_any<E>(sweep == 0 ? q : aR, sweep == 0 ? nullptr : cR, k, last ? v : nullptr, aL, cL,
-                         last ? y : nullptr, dm, s, cr_min, st);
+                         last ? y : nullptr, nullptr, dm, s, cr_min, st);
     if (rc) return rc;
     phase_mark(st, last ? "l_update_last" : "l_update");
     rc = l_update_any<E>(q, aL, cL, last ? y : nullptr, last ? nullptr : aR, last ? nullptr : cR, last ? out : nullptr,
@@ -243,7 +243,7 @@ int attention_impl(const void* q_, const void* k_, const void* v_, void* out_, i
   }
   if (recompute) {
     phase_mark(st, "first_frame");
-    rc = first_frame_any<E>(q, k, v, out, ws + w.ff, w.total - w.ff, dm, st);
+    rc = first_frame_any<E>(q, k, v, out, nullptr, ws + w.ff, w.total - w.ff, dm, st);
     if (rc) return rc;
   }
   phase_mark(st, nullptr);
@@ -251,15 +251,16 @@ int attention_impl(const void* q_, const void* k_, const void* v_, void* out_, i
 }
 
 template <typename E>
-int r_update_impl(const void* aR, const float* cR, const void* k, const void* v, void* aL, float* cL, void* y, int B,
-                  int heads, int T, int Hs, int Ws, int d, float row_scale, float cr_min, void* stream) {
+int r_update_impl(const void* aR, const float* cR, const void* k, const void* v, void* aL, float* cL, void* y,
+                  float* lse, int B, int heads, int T, int Hs, int Ws, int d, float row_scale, float cr_min,
+                  void* stream) {
   if (!aR || !k || !aL || !cL) return fail(VMONARCH_ERR_INVALID_ARG, "null tensor pointer");
   if ((v == nullptr) != (y == nullptr)) return fail(VMONARCH_ERR_INVALID_ARG, "v and y_out must be given together");
   if (!(row_scale > 0.f) || !(cr_min >= 0.f)) return fail(VMONARCH_ERR_INVALID_ARG, "row_scale must be > 0 and cr_min >= 0");
   Dims dm;
   int rc = make_dims(B, heads, T, Hs, Ws, d, &dm);
   if (rc) return rc;
-  return r_update_any<E>((const E*)aR, cR, (const E*)k, (const E*)v, (E*)aL, cL, (E*)y, dm, row_scale, cr_min,
+  return r_update_any<E>((const E*)aR, cR, (const E*)k, (const E*)v, (E*)aL, cL, (E*)y, lse, dm, row_scale, cr_min,
                          (hipStream_t)stream);
 }
 
@@ -278,8 +279,8 @@ int l_update_impl(const void* q, const void* aL, const float* cL, const void* y,
 }
 
 template <typename E>
-int first_frame_impl(const void* q, const void* k, const void* v, void* out, int B, int heads, int T, int Hs, int Ws,
-                     int d, void* stream) {
+int first_frame_impl(const void* q, const void* k, const void* v, void* out, float* lse, int B, int heads, int T,
+                     int Hs, int Ws, int d, void* stream) {
   if (!q || !k || !v || !out) return fail(VMONARCH_ERR_INVALID_ARG, "null tensor pointer");
   Dims dm;
   int rc = make_dims(B, heads, T, Hs, Ws, d, &dm);
@@ -293,7 +294,7 @@ int first_frame_impl(const void* q, const void* k, const void* v, void* out, int
       if (!scratch) return rc;
     }
   }
-  return first_frame_any<E>((const E*)q, (const E*)k, (const E*)v, (E*)out, scratch, sb, dm, (hipStream_t)stream);
+  return first_frame_any<E>((const E*)q, (const E*)k, (const E*)v, (E*)out, lse, scratch, sb, dm, (hipStream_t)stream);
 }
 
 }  // namespace
@@ -388,12 +389,28 @@ int vmonarch_attention_f32(const void* q, const void* k, const void* v, void* ou
 int vmonarch_r_update(const void* aR, const float* cR, const void* k, const void* v, void* aL_out, float* cL_out,
                       void* y_out, int B, int heads, int T, int Hs, int Ws, int d, float row_scale, float cr_min,
                       void* stream) {
-  return r_update_impl<bf16_t>(aR, cR, k, v, aL_out, cL_out, y_out, B, heads, T, Hs, Ws, d, row_scale, cr_min, stream);
+  return r_update_impl<bf16_t>(aR, cR, k, v, aL_out, cL_out, y_out, nullptr, B, heads, T, Hs, Ws, d, row_scale, cr_min,
+                               stream);
 }
 int vmonarch_r_update_f32(const void* aR, const float* cR, const void* k, const void* v, void* aL_out, float* cL_out,
                           void* y_out, int B, int heads, int T, int Hs, int Ws, int d, float row_scale, float cr_min,
                           void* stream) {
-  return r_update_impl<float>(aR, cR, k, v, aL_out, cL_out, y_out, B, heads, T, Hs, Ws, d, row_scale, cr_min, stream);
+  return r_update_impl<float>(aR, cR, k, v, aL_out, cL_out, y_out, nullptr, B, heads, T, Hs, Ws, d, row_scale, cr_min,
+                              stream);
+}
+int vmonarch_r_update_lse(const void* aR, const float* cR, const void* k, const void* v, void* aL_out, float* cL_out,
+                          void* y_out, float* lse_out, int B, int heads, int T, int Hs, int Ws, int d, float row_scale,
+                          float cr_min, void* stream) {
+  if (!lse_out) return fail(VMONARCH_ERR_INVALID_ARG, "null lse_out");
+  return r_update_impl<bf16_t>(aR, cR, k, v, aL_out, cL_out, y_out, lse_out, B, heads, T, Hs, Ws, d, row_scale, cr_min,
+                               stream);
+}
+int vmonarch_r_update_lse_f32(const void* aR, const float* cR, const void* k, const void* v, void* aL_out,
+                              float* cL_out, void* y_out, float* lse_out, int B, int heads, int T, int Hs, int Ws,
+                              int d, float row_scale, float cr_min, void* stream) {
+  if (!lse_out) return fail(VMONARCH_ERR_INVALID_ARG, "null lse_out");
+  return r_update_impl<float>(aR, cR, k, v, aL_out, cL_out, y_out, lse_out, B, heads, T, Hs, Ws, d, row_scale, cr_min,
+                              stream);
 }
 
 int vmonarch_l_update(const void* q, const void* aL, const float* cL, const void* y, void* aR_out, float* cR_out,
@@ -407,11 +424,21 @@ int vmonarch_l_update_f32(const void* q, const void* aL, const float* cL, const 
 
 int vmonarch_first_frame_attention(const void* q, const void* k, const void* v, void* out, int B, int heads, int T,
                                    int Hs, int Ws, int d, void* stream) {
-  return first_frame_impl<bf16_t>(q, k, v, out, B, heads, T, Hs, Ws, d, stream);
+  return first_frame_impl<bf16_t>(q, k, v, out, nullptr, B, heads, T, Hs, Ws, d, stream);
 }
 int vmonarch_first_frame_attention_f32(const void* q, const void* k, const void* v, void* out, int B, int heads, int T,
                                        int Hs, int Ws, int d, void* stream) {
-  return first_frame_impl<float>(q, k, v, out, B, heads, T, Hs, Ws, d, stream);
+  return first_frame_impl<float>(q, k, v, out, nullptr, B, heads, T, Hs, Ws, d, stream);
+}
+int vmonarch_first_frame_attention_lse(const void* q, const void* k, const void* v, void* out, float* lse_out, int B,
+                                       int heads, int T, int Hs, int Ws, int d, void* stream) {
+  if (!lse_out) return fail(VMONARCH_ERR_INVALID_ARG, "null lse_out");
+  return first_frame_impl<bf16_t>(q, k, v, out, lse_out, B, heads, T, Hs, Ws, d, stream);
+}
+int vmonarch_first_frame_attention_lse_f32(const void* q, const void* k, const void* v, void* out, float* lse_out,
+                                           int B, int heads, int T, int Hs, int Ws, int d, void* stream) {
+  if (!lse_out) return fail(VMONARCH_ERR_INVALID_ARG, "null lse_out");
+  return first_frame_impl<float>(q, k, v, out, lse_out, B, heads, T, Hs, Ws, d, stream);
 }
 
 int vmonarch_index_maps(int T, int Hs, int Ws, int32_t* perm_host, int32_t* inv_host) {

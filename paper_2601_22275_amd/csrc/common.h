@@ -70,23 +70,25 @@ struct Dims {
 // generic.hip : plain-ALU kernels, any T, b, d <= 256, element type float or bf16
 template <typename E>
 hipError_t launch_r_update_generic(const E* aR, const float* cR, const E* k, const E* v, E* aL, float* cL,
-                                   E* y, const Dims& dm, float row_scale, float cr_min, hipStream_t st);
+                                   E* y, float* lse, const Dims& dm, float row_scale, float cr_min, hipStream_t st);
 template <typename E>
 hipError_t launch_l_update_generic(const E* q, const E* aL, const float* cL, const E* y, E* aR, float* cR,
                                    E* out, const Dims& dm, float q_scale, hipStream_t st);
 template <typename E>
-hipError_t launch_first_frame_generic(const E* q, const E* k, const E* v, E* out, const Dims& dm, hipStream_t st);
+hipError_t launch_first_frame_generic(const E* q, const E* k, const E* v, E* out, float* lse, const Dims& dm,
+                                      hipStream_t st);
 hipError_t launch_permute_tokens(const void* in, void* out, const Dims& dm, int row_bytes, int to_pos_major,
                                  hipStream_t st);
 
 // flash.hip : bf16 MFMA blocked-softmax kernels (d == 64 or 128)
 bool flash_supported(const Dims& dm);
+// lse (optional, may be null): natural-log sum-exp of every query row's logits
 hipError_t launch_r_update_flash(const bf16_t* aR, const float* cR, const bf16_t* k, const bf16_t* v, bf16_t* aL,
-                                 float* cL, bf16_t* y, const Dims& dm, float row_scale, float cr_min,
+                                 float* cL, bf16_t* y, float* lse, const Dims& dm, float row_scale, float cr_min,
                                  int entropy_mode, hipStream_t st);
 size_t first_frame_flash_scratch_bytes(const Dims& dm);
-hipError_t launch_first_frame_flash(const bf16_t* q, const bf16_t* k, const bf16_t* v, bf16_t* out, void* scratch,
-                                    size_t scratch_bytes, const Dims& dm, hipStream_t st);
+hipError_t launch_first_frame_flash(const bf16_t* q, const bf16_t* k, const bf16_t* v, bf16_t* out, float* lse,
+                                    void* scratch, size_t scratch_bytes, const Dims& dm, hipStream_t st);
 
 // lpass.hip : bf16 MFMA temporal kernels (d == 64 or 128, T <= 128)
 bool lpass_supported(const Dims& dm);

@@ -51,6 +51,7 @@ struct FlashParams {
   bf16_t* outk;         // softmax(z) K   (alpha_L)
   bf16_t* outv;         // softmax(z) V   (y, or the first-frame output)
   float* cl;            // sum p log p    (c_L)
+  float* lse;           // natural-log sum-exp of the row's logits, or null
   float* part_o;        // split mode: [split][problem][nq][D] normalised partial outputs
   float* part_lse;      // split mode: [split][problem][nq] log2-sum-exp of the partial
   long long q_rows_per_problem;  // row distance between problems in q / cR / outputs
@@ -442,6 +443,7 @@ __global__ void __launch_bounds__(64 * NW) flash_kernel(FlashParams P) {
     const float inv = lt > 0.f ? 1.0f / lt : 0.f;
     const long long row = qrow0 + qrow[qt];
     if (!SPLIT) {
+      if (P.lse != nullptr && qvalid[qt] && g == 0) P.lse[row] = LN2 * (msc[qt] + __log2f(lt));
       if (ENT == 1) {
         // App. B: H = log S - L / S; here in base-2 units, c_L = -H
         float h = hsum[qt] + __shfl_xor(hsum[qt], 32);
@@ -517,8 +519,8 @@ __global__ void __launch_bounds__(64 * NW) flash_kernel(FlashParams P) {
 // Merge of the key-range partials of the first-frame recomputation: weights 2^(lse - max).
 __global__ void __launch_bounds__(128) merge_splits_kernel(const float* __restrict__ part_o,
                                                            const float* __restrict__ part_lse, bf16_t* __restrict__ out,
-                                                           int nsplit, long long rows_per_split, int nq,
-                                                           long long out_rows_per_problem) {
+                                                           float* __restrict__ lse, int nsplit, long long rows_per_split,
+                                                           int nq, long long out_rows_per_problem) {
   const int D = blockDim.x;        // one thread per channel
   const long long r = blockIdx.x;  // problem * nq + row
   const int c = threadIdx.x;       // channel
@@ -533,6 +535,7 @@ __global__ void __launch_bounds__(128) merge_splits_kernel(const float* __restri
     acc += w * part_o[(s * rows_per_split + r) * D + c];
   }
   out[(prob * out_rows_per_problem + row) * D + c] = f32_to_bf16(acc / wsum);
+  if (lse != nullptr && c == 0) lse[prob * out_rows_per_problem + row] = LN2 * (mx + log2f(wsum));
 }
 
 template <int D, bool OUT_K, bool OUT_V, int ENT, bool SPLIT>
@@ -567,10 +570,10 @@ int first_frame_splits(const Dims& dm) {
 bool flash_supported(const Dims& dm) { return dm.d == 128 || dm.d == 64; }
 
 hipError_t launch_r_update_flash(const bf16_t* aR, const float* cR, const bf16_t* k, const bf16_t* v, bf16_t* aL,
-                                 float* cL, bf16_t* y, const Dims& dm, float row_scale, float cr_min, int entropy_mode,
-                                 hipStream_t st) {
+                                 float* cL, bf16_t* y, float* lse, const Dims& dm, float row_scale, float cr_min,
+                                 int entropy_mode, hipStream_t st) {
   FlashParams P = {};
-  P.q = aR; P.cR = cR; P.k = k; P.v = v; P.outk = aL; P.outv = y; P.cl = cL;
+  P.q = aR; P.cR = cR; P.k = k; P.v = v; P.outk = aL; P.outv = y; P.cl = cL; P.lse = lse;
   P.q_rows_per_problem = dm.b; P.k_rows_per_problem = dm.b;
   P.nq = dm.b; P.nk = dm.b;
   P.nqb = (dm.b + BQ - 1) / BQ;
@@ -593,6 +596,7 @@ hipError_t launch_r_update_flash(const bf16_t* aR, const float* cR, const bf16_t
     if (e != hipSuccess || v == nullptr) return e;
     P.outk = nullptr;
     P.cl = nullptr;
+    P.lse = nullptr;
     return launch_flash<D, false, true, 0, false>(P, st);
   };
   return dm.d == 128 ? run(std::integral_constant<int, 128>{}) : run(std::integral_constant<int, 64>{});
@@ -605,11 +609,12 @@ size_t first_frame_flash_scratch_bytes(const Dims& dm) {
   return rows * dm.d * sizeof(float) + ((rows * sizeof(float) + 255) & ~(size_t)255);
 }
 
-hipError_t launch_first_frame_flash(const bf16_t* q, const bf16_t* k, const bf16_t* v, bf16_t* out, void* scratch,
-                                    size_t scratch_bytes, const Dims& dm, hipStream_t st) {
+hipError_t launch_first_frame_flash(const bf16_t* q, const bf16_t* k, const bf16_t* v, bf16_t* out, float* lse,
+                                    void* scratch, size_t scratch_bytes, const Dims& dm, hipStream_t st) {
   FlashParams P = {};
   const int ns = first_frame_splits(dm);
   P.q = q; P.cR = nullptr; P.k = k; P.v = v; P.outk = nullptr; P.outv = out; P.cl = nullptr;
+  P.lse = lse;  // written by the kernel itself when one key range covers everything, else by the merge
   P.q_rows_per_problem = dm.N; P.k_rows_per_problem = dm.N;
   P.nq = dm.b;
   if (dm.N > 0x7fffffffLL - BK) return hipErrorInvalidValue;
@@ -634,7 +639,7 @@ hipError_t launch_first_frame_flash(const bf16_t* q, const bf16_t* k, const bf16
   hipError_t e = d128 ? launch_flash<128, false, true, 0, true>(P, st) : launch_flash<64, false, true, 0, true>(P, st);
   if (e != hipSuccess) return e;
   hipLaunchKernelGGL(merge_splits_kernel, dim3((unsigned)((long long)dm.BH * dm.b)), dim3(dm.d), 0, st, P.part_o,
-                     P.part_lse, out, ns, (long long)dm.BH * dm.b, dm.b, dm.N);
+                     P.part_lse, out, lse, ns, (long long)dm.BH * dm.b, dm.b, dm.N);
   return hipGetLastError();
 }
 

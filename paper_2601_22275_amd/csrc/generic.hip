@@ -30,11 +30,13 @@ __device__ __forceinline__ EntState ent_merge(EntState a, EntState c) {
 
 // One wave (64 lanes) per query row.  nk keys starting at kbase (and vbase) with row
 // stride d.  Emits out_k = softmax(z) K (if OUT_K), out_v = softmax(z) V (if OUT_V) and
-// cl = sum p log p (if cl != nullptr), with z = scale * (qrow . K[l]).
+// cl = sum p log p (if cl != nullptr) and lse = log sum exp z (if lse != nullptr), with
+// z = scale * (qrow . K[l]).
 template <typename E, bool OUT_K, bool OUT_V>
 __device__ void attend_row(const E* __restrict__ qrow, float scale, const E* __restrict__ kbase,
                            const E* __restrict__ vbase, long long nk, int d, E* __restrict__ out_k,
-                           E* __restrict__ out_v, float* __restrict__ cl, float* sq, float* sp) {
+                           E* __restrict__ out_v, float* __restrict__ cl, float* __restrict__ lse, float* sq,
+                           float* sp) {
   const int lane = threadIdx.x;
   for (int c = lane; c < d; c += 64) sq[c] = load_f<E>(qrow + c);
   __syncthreads();
@@ -67,6 +69,7 @@ __device__ void attend_row(const E* __restrict__ qrow, float scale, const E* __r
   const float lse_shift = st.m;
   const float inv_S = 1.f / st.S;
   if (cl != nullptr && lane == 0) *cl = -(logf(st.S) - st.L * inv_S);  // c_L = -H
+  if (lse != nullptr && lane == 0) *lse = st.m + logf(st.S);
   // pass 2: out = sum_l p_l row_l, 64 keys at a time through LDS
   float acck[kMaxD / 64], accv[kMaxD / 64];
 #pragma unroll
@@ -110,8 +113,8 @@ template <typename E, bool HAS_V>
 __global__ void __launch_bounds__(64) r_update_generic_kernel(const E* __restrict__ aR, const float* __restrict__ cR,
                                                               const E* __restrict__ k, const E* __restrict__ v,
                                                               E* __restrict__ aL, float* __restrict__ cL,
-                                                              E* __restrict__ y, int T, int b, int d,
-                                                              float row_scale, float cr_min) {
+                                                              E* __restrict__ y, float* __restrict__ lse, int T, int b,
+                                                              int d, float row_scale, float cr_min) {
   __shared__ float sq[kMaxD];
   __shared__ float sp[64];
   const int i = blockIdx.x, kf = blockIdx.y, bh = blockIdx.z;
@@ -120,20 +123,21 @@ __global__ void __launch_bounds__(64) r_update_generic_kernel(const E* __restric
   float c = cR ? cR[row] : 1.f;
   c = fmaxf(c, cr_min);
   attend_row<E, true, HAS_V>(aR + row * d, row_scale / c, k + frame0 * d, HAS_V ? v + frame0 * d : nullptr, b, d,
-                             aL + row * d, HAS_V ? y + row * d : nullptr, cL + row, sq, sp);
+                             aL + row * d, HAS_V ? y + row * d : nullptr, cL + row, lse ? lse + row : nullptr, sq, sp);
 }
 
 template <typename E>
 __global__ void __launch_bounds__(64) first_frame_generic_kernel(const E* __restrict__ q, const E* __restrict__ k,
-                                                                 const E* __restrict__ v, E* __restrict__ out, int T,
-                                                                 int b, int d, float scale) {
+                                                                 const E* __restrict__ v, E* __restrict__ out,
+                                                                 float* __restrict__ lse, int T, int b, int d,
+                                                                 float scale) {
   __shared__ float sq[kMaxD];
   __shared__ float sp[64];
   const int i = blockIdx.x, bh = blockIdx.y;
   const long long N = (long long)T * b;
   const long long head0 = (long long)bh * N;
   attend_row<E, false, true>(q + (head0 + i) * d, scale, k + head0 * d, v + head0 * d, N, d, nullptr,
-                             out + (head0 + i) * d, nullptr, sq, sp);
+                             out + (head0 + i) * d, nullptr, lse ? lse + head0 + i : nullptr, sq, sp);
 }
 
 // One workgroup per (position i, batch*head).  The T x T block L_i lives in LDS.
@@ -220,13 +224,13 @@ __global__ void __launch_bounds__(256) permute_tokens_kernel(const uint32_t* __r
 
 template <typename E>
 hipError_t launch_r_update_generic(const E* aR, const float* cR, const E* k, const E* v, E* aL, float* cL, E* y,
-                                   const Dims& dm, float row_scale, float cr_min, hipStream_t st) {
+                                   float* lse, const Dims& dm, float row_scale, float cr_min, hipStream_t st) {
   dim3 grid(dm.b, dm.T, dm.BH);
   if (v != nullptr)
-    hipLaunchKernelGGL((r_update_generic_kernel<E, true>), grid, dim3(64), 0, st, aR, cR, k, v, aL, cL, y, dm.T, dm.b,
-                       dm.d, row_scale, cr_min);
+    hipLaunchKernelGGL((r_update_generic_kernel<E, true>), grid, dim3(64), 0, st, aR, cR, k, v, aL, cL, y, lse, dm.T,
+                       dm.b, dm.d, row_scale, cr_min);
   else
-    hipLaunchKernelGGL((r_update_generic_kernel<E, false>), grid, dim3(64), 0, st, aR, cR, k, v, aL, cL, y, dm.T,
+    hipLaunchKernelGGL((r_update_generic_kernel<E, false>), grid, dim3(64), 0, st, aR, cR, k, v, aL, cL, y, lse, dm.T,
                        dm.b, dm.d, row_scale, cr_min);
   return hipGetLastError();
 }
@@ -256,9 +260,10 @@ hipError_t launch_l_update_generic(const E* q, const E* aL, const float* cL, con
 }
 
 template <typename E>
-hipError_t launch_first_frame_generic(const E* q, const E* k, const E* v, E* out, const Dims& dm, hipStream_t st) {
+hipError_t launch_first_frame_generic(const E* q, const E* k, const E* v, E* out, float* lse, const Dims& dm,
+                                      hipStream_t st) {
   dim3 grid(dm.b, dm.BH);
-  hipLaunchKernelGGL((first_frame_generic_kernel<E>), grid, dim3(64), 0, st, q, k, v, out, dm.T, dm.b, dm.d,
+  hipLaunchKernelGGL((first_frame_generic_kernel<E>), grid, dim3(64), 0, st, q, k, v, out, lse, dm.T, dm.b, dm.d,
                      1.0f / sqrtf((float)dm.d));
   return hipGetLastError();
 }
@@ -275,16 +280,16 @@ hipError_t launch_permute_tokens(const void* in, void* out, const Dims& dm, int 
 }
 
 template hipError_t launch_r_update_generic<float>(const float*, const float*, const float*, const float*, float*,
-                                                   float*, float*, const Dims&, float, float, hipStream_t);
+                                                   float*, float*, float*, const Dims&, float, float, hipStream_t);
 template hipError_t launch_r_update_generic<bf16_t>(const bf16_t*, const float*, const bf16_t*, const bf16_t*, bf16_t*,
-                                                    float*, bf16_t*, const Dims&, float, float, hipStream_t);
+                                                    float*, bf16_t*, float*, const Dims&, float, float, hipStream_t);
 template hipError_t launch_l_update_generic<float>(const float*, const float*, const float*, const float*, float*,
                                                    float*, float*, const Dims&, float, hipStream_t);
 template hipError_t launch_l_update_generic<bf16_t>(const bf16_t*, const bf16_t*, const float*, const bf16_t*, bf16_t*,
                                                     float*, bf16_t*, const Dims&, float, hipStream_t);
-template hipError_t launch_first_frame_generic<float>(const float*, const float*, const float*, float*, const Dims&,
-                                                      hipStream_t);
-template hipError_t launch_first_frame_generic<bf16_t>(const bf16_t*, const bf16_t*, const bf16_t*, bf16_t*,
+template hipError_t launch_first_frame_generic<float>(const float*, const float*, const float*, float*, float*,
+                                                      const Dims&, hipStream_t);
+template hipError_t launch_first_frame_generic<bf16_t>(const bf16_t*, const bf16_t*, const bf16_t*, bf16_t*, float*,
                                                        const Dims&, hipStream_t);
 
 }  // namespace vm

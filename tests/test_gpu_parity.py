@@ -107,6 +107,40 @@ def test_r_update_matches_oracle(env, T, Hs, Ws, d, dt, with_v, with_cr, mode):
             assert U.rel_l2(gy, ref_y) <= rel_tol and U.max_abs(gy, ref_y) <= abs_tol
 
 
+@pytest.mark.parametrize("T,Hs,Ws,d,dt", [(4, 4, 4, 32, "f32"), (3, 10, 30, 128, "bf16"), (2, 3, 11, 64, "bf16"),
+                                           (2, 9, 9, 96, "bf16")])
+def test_r_update_log_sum_exp_output(env, T, Hs, Ws, d, dt):
+    """lse = log sum_l exp z from the definition; the entropy identity c_L = sum_l R z - lse ties it
+    to the other two outputs."""
+    torch, binding, dev = env
+    bf16 = dt == "bf16"
+    b, heads = Hs * Ws, 2
+    rng = np.random.default_rng(77)
+    data = U.structured_heads(T, Hs, Ws, d, 15, heads, bf16)
+    aR = [h[0] for h in data]; K = [h[1] for h in data]
+    cR = (0.05 + 2.0 * rng.random((heads, T * b))).astype(np.float32)
+    row_scale, cr_min = 1.0 / math.sqrt(d), 0.1
+    taR, tK = U.to_device(aR, torch, dev), U.to_device(K, torch, dev)
+    tcR = torch.from_numpy(cR).to(dev).view(1, heads, -1)
+    aL, cL, _, lse = binding.r_update_lse(taR, tcR, tK, None, T, Hs, Ws, row_scale, cr_min)
+    aL2, cL2, _ = binding.r_update(taR, tcR, tK, None, T, Hs, Ws, row_scale, cr_min)
+    assert torch.equal(aL, aL2) and torch.equal(cL, cL2)      # the extra output changes nothing else
+    glse, gcL, gaL = U.from_device(lse), U.from_device(cL), U.from_device(aL)
+    for h in range(heads):
+        a = U.to_f64(aR[h]).reshape(T, b, d)
+        kk = U.to_f64(K[h]).reshape(T, b, d)
+        z = np.einsum("kid,kld->kil", a, kk) * row_scale / np.maximum(cR[h].reshape(T, b, 1).astype(np.float64), cr_min)
+        zmax = z.max(axis=2, keepdims=True)
+        ref = (zmax[..., 0] + np.log(np.exp(z - zmax).sum(axis=2))).reshape(T * b)
+        err = U.max_abs(glse[h], ref)
+        print(f"r_update_lse T={T} b={b} d={d} {dt}: lse max err {err:.2e}")
+        assert err <= (5e-3 if bf16 else 1e-4)
+        # sum_l R_l z_l = scale / c * aR . alpha_L  (z is linear in K): c_L + lse equals it
+        mean_z = (a * gaL[h].reshape(T, b, d)).sum(axis=2).reshape(T * b) * row_scale / np.maximum(cR[h], cr_min)
+        # (alpha_L carries a relative bf16 rounding error, and |z| grows like 1 / c_R)
+        np.testing.assert_allclose(gcL[h] + glse[h], mean_z, rtol=2.0 ** -7 if bf16 else 1e-4, atol=2e-2 if bf16 else 1e-3)
+
+
 # ------------------------------------------------------------------ L-update per factor
 L_CASES = [
     (4, 4, 4, 32, "f32"), (7, 1, 5, 20, "f32"), (5, 2, 3, 96, "bf16"),
@@ -176,6 +210,31 @@ def test_first_frame_attention_matches_oracle(env, T, Hs, Ws, d, dt):
         print(f"first_frame T={T} b={b} d={d} {dt}: rel {U.rel_l2(got[h][:b], ref):.2e} max {U.max_abs(got[h][:b], ref):.2e}")
         assert U.rel_l2(got[h][:b], ref) <= rel_tol and U.max_abs(got[h][:b], ref) <= abs_tol
         assert (got[h][b:] == 7.0).all()          # nothing beyond frame 0 is written
+
+
+@pytest.mark.parametrize("T,Hs,Ws,d,dt", [(4, 4, 4, 32, "f32"), (1, 3, 3, 128, "bf16"), (9, 7, 9, 128, "bf16"),
+                                           (40, 16, 16, 64, "bf16")])
+def test_first_frame_log_sum_exp_output(env, T, Hs, Ws, d, dt):
+    """(1, 3, 3): one key range, written by the kernel; (40, 16, 16): several ranges, written by the merge."""
+    torch, binding, dev = env
+    bf16 = dt == "bf16"
+    b, heads = Hs * Ws, 2
+    data = U.structured_heads(T, Hs, Ws, d, 16, heads, bf16)
+    tq, tk, tv = (U.to_device([h[i] for h in data], torch, dev) for i in range(3))
+    out, out2 = torch.zeros_like(tq), torch.zeros_like(tq)
+    _, lse = binding.first_frame_attention_lse(tq, tk, tv, T, Hs, Ws, out)
+    binding.first_frame_attention(tq, tk, tv, T, Hs, Ws, out2)
+    assert torch.equal(out, out2)
+    glse = U.from_device(lse)
+    for h in range(heads):
+        q, k = U.to_f64(data[h][0])[:b], U.to_f64(data[h][1])
+        z = q @ k.T / math.sqrt(d)
+        zmax = z.max(axis=1, keepdims=True)
+        ref = zmax[:, 0] + np.log(np.exp(z - zmax).sum(axis=1))
+        err = U.max_abs(glse[h][:b], ref)
+        print(f"first_frame_lse T={T} b={b} d={d} {dt}: lse max err {err:.2e}")
+        assert err <= (5e-3 if bf16 else 1e-4)
+        assert (glse[h][b:] == 0.0).all()
 
 
 # ------------------------------------------------------------------ whole path
