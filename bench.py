@@ -67,6 +67,31 @@ def cpu_baseline(wl, q_bits, k_bits, v_bits, positions=1024, rows=1024, min_seco
     }
 
 
+def mfma_probe(torch, binding, dev, cus=256, iters=20000):
+    """Sustained rate of the bare bf16 matrix instruction with nothing else running, on all-zero and on
+    random-normal operands: the device's matrix pipe is power-limited, so the second figure, not the
+    published peak, is what a kernel fed with real data can reach at best."""
+    res = {}
+    g = torch.Generator(device="cpu")
+    g.manual_seed(7)
+    for name in ("zeros", "random_normal"):
+        n = cus * 512 * 64
+        ops = torch.zeros(n, dtype=torch.bfloat16) if name == "zeros" else torch.randn(n, generator=g).to(torch.bfloat16)
+        ops = ops.to(dev)
+        binding.mfma_probe(ops, cus, 1000)
+        torch.cuda.synchronize()
+        best = float("inf")
+        for _ in range(3):
+            e0, e1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+            e0.record()
+            _, fl = binding.mfma_probe(ops, cus, iters)
+            e1.record()
+            torch.cuda.synchronize()
+            best = min(best, e0.elapsed_time(e1))
+        res[name] = fl / (best * 1e-3) / 1e12
+    return res
+
+
 def recorded_traffic():
     """HBM bytes per launch of the dominant kernel from the committed rocprofv3 --pmc summary
     (FETCH_SIZE and WRITE_SIZE runs scaled by a copy of known size), or None."""
@@ -229,6 +254,11 @@ def main() -> int:
         # reads and writes B*heads*N*d*elem bytes each: the yardstick for FETCH_SIZE / WRITE_SIZE
         binding.permute_tokens(tq, wl.T, wl.Hs, wl.Ws, True)
         torch.cuda.synchronize()
+
+    probe = mfma_probe(torch, binding, dev, torch.cuda.get_device_properties(0).multi_processor_count)
+    if roofline is not None:
+        roofline["sustained_mfma_tflops"] = probe
+        roofline["frac_of_sustained_random"] = roofline["achieved"] / probe["random_normal"]
 
     cpu = None
     if not args.no_cpu_baseline and bf16:

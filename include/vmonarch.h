@@ -184,6 +184,19 @@ int vmonarch_index_maps(int T, int Hs, int Ws, int32_t* perm_host, int32_t* inv_
 int vmonarch_permute_tokens(const void* in, void* out, int B, int heads, int T, int Hs, int Ws,
                             int row_bytes, int to_position_major, void* stream);
 
+/*
+ * Benchmark aid: the sustained rate of the bf16 matrix instruction the MFMA kernels are built
+ * on (v_mfma_f32_32x32x16_bf16) with nothing else running, on operand data the caller
+ * supplies.  Launches `blocks` workgroups of 8 waves; every lane reads 8 x 16 bytes from
+ * `operands` (device, blocks * 512 * 128 bytes: 4 A and 4 B operands per lane) and issues
+ * 8 * iters MFMAs on four accumulators; one float per lane goes to `out` (device,
+ * blocks * 512 floats) so that the work is not optimised away.  *flops_host (HOST, may be
+ * NULL) receives the floating-point operations of the launch.  The matrix pipe is
+ * power-limited: the rate measured with random operands is lower than with zeros.
+ */
+int vmonarch_mfma_probe(const void* operands, float* out, int blocks, int iters, double* flops_host,
+                        void* stream);
+
 #ifdef __cplusplus
 }
 #endif

@@ -29,7 +29,7 @@ EXPORTS = [
     "vmonarch_first_frame_attention", "vmonarch_first_frame_attention_f32", "vmonarch_index_maps",
     "vmonarch_permute_tokens", "vmonarch_set_phase_timing", "vmonarch_get_phase_timing",
     "vmonarch_r_update_lse", "vmonarch_r_update_lse_f32", "vmonarch_first_frame_attention_lse",
-    "vmonarch_first_frame_attention_lse_f32",
+    "vmonarch_first_frame_attention_lse_f32", "vmonarch_mfma_probe",
 ]
 
 
@@ -71,6 +71,7 @@ def lib() -> ctypes.CDLL:
             getattr(L, name).argtypes = [c_void_p] * 7 + dims + [c_float, c_void_p]
         for name in ("vmonarch_first_frame_attention", "vmonarch_first_frame_attention_f32"):
             getattr(L, name).argtypes = [c_void_p] * 4 + dims + [c_void_p]
+        L.vmonarch_mfma_probe.argtypes = [c_void_p, c_void_p, c_int, c_int, c_void_p, c_void_p]
         L.vmonarch_index_maps.argtypes = [c_int, c_int, c_int, c_void_p, c_void_p]
         L.vmonarch_permute_tokens.argtypes = [c_void_p, c_void_p, c_int, c_int, c_int, c_int, c_int, c_int, c_int,
                                               c_void_p]
@@ -215,6 +216,16 @@ def first_frame_attention_lse(q, k, v, T, Hs, Ws, out):
     fn = getattr(lib(), "vmonarch_first_frame_attention_lse" + _suffix(q))
     _check(fn(_ptr(q), _ptr(k), _ptr(v), _ptr(out), _ptr(lse), B, heads, T, Hs, Ws, d, _stream()))
     return out, lse
+
+
+def mfma_probe(operands, blocks, iters):
+    """Launches the matrix-instruction probe on `operands` (uint8/bf16 device tensor of blocks*512*128 bytes);
+    returns (out tensor, floating-point operations of the launch)."""
+    assert operands.numel() * operands.element_size() >= blocks * 512 * 128
+    out = torch.empty(blocks * 512, dtype=torch.float32, device=operands.device)
+    fl = ctypes.c_double(0.0)
+    _check(lib().vmonarch_mfma_probe(_ptr(operands), _ptr(out), blocks, iters, ctypes.byref(fl), _stream()))
+    return out, fl.value
 
 
 def index_maps(T, Hs, Ws):

@@ -465,5 +465,13 @@ int vmonarch_permute_tokens(const void* in, void* out, int B, int heads, int T, 
   return e == hipSuccess ? VMONARCH_OK : hip_fail(e, "permute_tokens launch");
 }
 
+int vmonarch_mfma_probe(const void* operands, float* out, int blocks, int iters, double* flops_host, void* stream) {
+  if (!operands || !out) return fail(VMONARCH_ERR_INVALID_ARG, "null pointer");
+  if (blocks <= 0 || iters <= 0) return fail(VMONARCH_ERR_INVALID_ARG, "blocks and iters must be positive");
+  if (flops_host) *flops_host = (double)blocks * 8.0 * (double)iters * 8.0 * (2.0 * 32 * 32 * 16);
+  hipError_t e = launch_mfma_probe(operands, out, blocks, iters, (hipStream_t)stream);
+  return e == hipSuccess ? VMONARCH_OK : hip_fail(e, "mfma_probe launch");
+}
+
 #pragma GCC visibility pop
 }  // extern "C"

@@ -80,6 +80,8 @@ hipError_t launch_first_frame_generic(const E* q, const E* k, const E* v, E* out
 hipError_t launch_permute_tokens(const void* in, void* out, const Dims& dm, int row_bytes, int to_pos_major,
                                  hipStream_t st);
 
+hipError_t launch_mfma_probe(const void* operands, float* out, int blocks, int iters, hipStream_t st);
+
 // flash.hip : bf16 MFMA blocked-softmax kernels (d == 64 or 128)
 bool flash_supported(const Dims& dm);
 // lse (optional, may be null): natural-log sum-exp of every query row's logits

@@ -220,7 +220,44 @@ __global__ void __launch_bounds__(256) permute_tokens_kernel(const uint32_t* __r
   }
 }
 
+// Measurement aid: nothing but v_mfma_f32_32x32x16_bf16, eight per loop trip on four independent
+// accumulators, two waves per SIMD, on operand data supplied by the caller.  The sustained rate
+// depends on that data: the matrix pipe of this device is power-limited, and operands that
+// toggle more bits lower the clock.
+__global__ void __launch_bounds__(512) mfma_probe_kernel(const uint4* __restrict__ ops, float* __restrict__ out,
+                                                         int iters) {
+  bf16x8 a[4], b[4];
+#pragma unroll
+  for (int i = 0; i < 4; ++i) {
+    const uint4 x = ops[((size_t)blockIdx.x * 512 + threadIdx.x) * 8 + i];
+    const uint4 y = ops[((size_t)blockIdx.x * 512 + threadIdx.x) * 8 + 4 + i];
+    __builtin_memcpy(&a[i], &x, 16);
+    __builtin_memcpy(&b[i], &y, 16);
+  }
+  f32x16 c[4];
+#pragma unroll
+  for (int q = 0; q < 4; ++q)
+#pragma unroll
+    for (int i = 0; i < 16; ++i) c[q][i] = 0.f;
+  for (int it = 0; it < iters; ++it) {
+#pragma unroll
+    for (int j = 0; j < 8; ++j)
+      c[j & 3] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(a[j & 3], b[(j + (j >> 2)) & 3], c[j & 3], 0, 0, 0);
+  }
+  float s = 0.f;
+#pragma unroll
+  for (int q = 0; q < 4; ++q)
+#pragma unroll
+    for (int i = 0; i < 16; ++i) s += c[q][i];
+  out[(size_t)blockIdx.x * 512 + threadIdx.x] = s;
+}
+
 }  // namespace
+
+hipError_t launch_mfma_probe(const void* operands, float* out, int blocks, int iters, hipStream_t st) {
+  hipLaunchKernelGGL(mfma_probe_kernel, dim3(blocks), dim3(512), 0, st, (const uint4*)operands, out, iters);
+  return hipGetLastError();
+}
 
 template <typename E>
 hipError_t launch_r_update_generic(const E* aR, const float* cR, const E* k, const E* v, E* aL, float* cL, E* y,

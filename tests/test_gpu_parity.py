@@ -331,6 +331,17 @@ def test_user_workspace_is_used_and_checked(env):
         binding.set_workspace(None)
 
 
+def test_mfma_probe_runs_and_counts_its_work(env):
+    torch, binding, dev = env
+    blocks, iters = 4, 3
+    ops = torch.ones(blocks * 512 * 64, dtype=torch.bfloat16, device=dev)
+    out, fl = binding.mfma_probe(ops, blocks, iters)
+    assert fl == blocks * 8 * iters * 8 * 2 * 32 * 32 * 16
+    # all-ones operands: every accumulator element is 16 per MFMA; 8 * iters MFMAs over 4 accumulators of 16
+    # registers, summed per lane
+    assert torch.equal(out.cpu(), torch.full((blocks * 512,), float(16 * 8 * iters * 16)))
+
+
 def test_invalid_arguments_are_rejected_without_launching(env):
     torch, binding, dev = env
     L = binding.lib()
