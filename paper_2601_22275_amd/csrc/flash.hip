@@ -405,8 +405,14 @@ __global__ void __launch_bounds__(64 * NW) flash_kernel(FlashParams P) {
 #pragma unroll
         for (int c = 0; c < 2; ++c) pbB[qt][c] = zero;  // step 0 has no predecessor: it adds P^T = 0
     }
-    logits(smem, 0, sA);
-    look_ahead(sA);
+    // A wave whose 32 query rows all lie past the end of the problem (the tail of the last query
+    // block) only helps to load the tiles: it skips the arithmetic, and the energy it would burn
+    // on rows nobody reads (the matrix pipe is power-limited) goes to the waves that have work.
+    const bool active = qb * BQ + wave * (32 * QT) < P.nq;
+    if (active) {
+      logits(smem, 0, sA);
+      look_ahead(sA);
+    }
     const int last_left = nkeys - (ntiles - 1) * BK;  // 1..64 keys in the last tile
     // Four tiles per trip so that every LDS slot offset is an instruction immediate (tile t
     // sits in slot t & 3 and a trip starts at a multiple of four).
@@ -421,8 +427,10 @@ __global__ void __launch_bounds__(64 * NW) flash_kernel(FlashParams P) {
       const char* kt = smem + SLOT * TILE_BYTES;
       const char* kn = smem + ((SLOT + 1) & 3) * TILE_BYTES;
       const int left0 = t == ntiles - 1 ? last_left : 64;
-      step(sA, sB, pbB, pbA, kt, 1, kp, 1, left0);  // at t = 0: P^T = 0 against the cleared slot 3
-      step(sB, sA, pbA, pbB, kn, 0, kt, 0, left0 - 32);
+      if (active) {
+        step(sA, sB, pbB, pbA, kt, 1, kp, 1, left0);  // at t = 0: P^T = 0 against the cleared slot 3
+        step(sB, sA, pbA, pbB, kn, 0, kt, 0, left0 - 32);
+      }
     };
     for (int t0 = 0; t0 < ntiles; t0 += 4) {
       tile_iteration(std::integral_constant<int, 0>{}, t0);
@@ -430,7 +438,7 @@ __global__ void __launch_bounds__(64 * NW) flash_kernel(FlashParams P) {
       if (t0 + 2 < ntiles) tile_iteration(std::integral_constant<int, 2>{}, t0 + 2);
       if (t0 + 3 < ntiles) tile_iteration(std::integral_constant<int, 3>{}, t0 + 3);
     }
-    accumulate(smem + ((ntiles - 1) & 3) * TILE_BYTES, 1, pbB);  // drain: the products of the last sub-tile
+    if (active) accumulate(smem + ((ntiles - 1) & 3) * TILE_BYTES, 1, pbB);  // drain: the products of the last sub-tile
   }
   // ---- epilogue ----------------------------------------------------------------------------
   // Normalised rows are staged in LDS (each wave owns the 32 * QT rows it computed, swizzled
