@@ -154,6 +154,8 @@ def main() -> int:
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--copy-calibration", action="store_true",
                     help="also run one token-permutation copy of known size (reference for HBM byte counters)")
+    ap.add_argument("--graph", action="store_true",
+                    help="capture one call in a HIP graph and time replays (for launch-bound small workloads)")
     ap.add_argument("--sweep-frames", action="store_true",
                     help="time T = 20..48 frames of 28x52 tokens against exact dense attention instead of the benchmark")
     args = ap.parse_args()
@@ -193,8 +195,18 @@ def main() -> int:
     binding.set_workspace(ws)
     binding.set_entropy_mode(binding.ENTROPY_IDENTITY if args.entropy == "identity" else binding.ENTROPY_ONLINE)
 
-    def step():
+    def eager_step():
         binding.attention(tq, tk, tv, wl.T, wl.Hs, wl.Ws, wl.iters, wl.recompute, out=out)
+
+    step = eager_step
+    if args.graph:
+        # the call only enqueues kernels once the workspace is the caller's: capture it once, replay it
+        eager_step()
+        torch.cuda.synchronize()
+        graph = torch.cuda.CUDAGraph()
+        with torch.cuda.graph(graph):
+            eager_step()
+        step = graph.replay
 
     for _ in range(args.warmup):
         step()
@@ -219,7 +231,7 @@ def main() -> int:
     binding.set_phase_timing(True)
     phase_ms = {}
     for _ in range(args.steps):
-        step()
+        eager_step()
         for name, t in binding.get_phase_timing():
             phase_ms.setdefault(name, []).append(t)
     binding.set_phase_timing(False)
@@ -274,7 +286,8 @@ def main() -> int:
         "algorithmic_tflop_per_call": flops / 1e12,
         "config": {"workload": wl.name, "B": wl.B, "heads": wl.heads, "T": wl.T, "Hs": wl.Hs, "Ws": wl.Ws,
                    "N": wl.N, "d": wl.d, "iters": wl.iters, "recompute": bool(wl.recompute),
-                   "entropy": args.entropy, "input_generation_s": gen_s},
+                   "entropy": args.entropy, "launch": "hip graph replay" if args.graph else "eager",
+                   "input_generation_s": gen_s},
         "phase_ms": phases,
         "roofline": roofline,
         "hbm_phase": hbm_phase,

@@ -331,6 +331,60 @@ def test_user_workspace_is_used_and_checked(env):
         binding.set_workspace(None)
 
 
+def test_batch_and_head_axes_are_independent(env):
+    """[B][heads] is one flat axis of independent problems: a (2, 3) batch equals its six single runs."""
+    torch, binding, dev = env
+    T, Hs, Ws, d = 6, 9, 11, 128
+    data = U.structured_heads(T, Hs, Ws, d, 19, 6, True)
+    full = [torch.stack([torch.from_numpy(data[2 * bb + hh][i]).view(torch.bfloat16) for bb in range(3) for hh in range(2)])
+            .view(3, 2, T * Hs * Ws, d).to(dev) for i in range(3)]
+    got = binding.attention(full[0], full[1], full[2], T, Hs, Ws, 2, True)
+    for bb in range(3):
+        for hh in range(2):
+            one = [x[bb:bb + 1, hh:hh + 1].contiguous() for x in full]
+            assert torch.equal(binding.attention(one[0], one[1], one[2], T, Hs, Ws, 2, True)[0, 0], got[bb, hh])
+
+
+def test_whole_path_replays_from_a_hip_graph(env):
+    """With a caller workspace the call only enqueues kernels (no allocation, no synchronisation), so it
+    can be captured once and replayed; every replay, with fresh inputs in the same buffers and eager work
+    in between, must equal the eager result bit for bit."""
+    torch, binding, dev = env
+    T, Hs, Ws, d, heads = 8, 10, 13, 128, 2
+    N = T * Hs * Ws
+    sets = [U.structured_heads(T, Hs, Ws, d, 30 + r, heads, True) for r in range(3)]
+    def dev_inputs(r):
+        return [U.to_device([h[i] for h in sets[r]], torch, dev) for i in range(3)]
+    need = binding.workspace_bytes(1, heads, T, Hs, Ws, d, 2, True, 2)
+    ws = torch.empty(need, dtype=torch.uint8, device=dev)
+    binding.set_workspace(ws)
+    try:
+        sq, sk, sv = dev_inputs(0)
+        sout = torch.empty_like(sq)
+        eager = [binding.attention(*dev_inputs(r), T, Hs, Ws, 2, True).clone() for r in range(3)]  # also warms up
+        torch.cuda.synchronize()
+        side = torch.cuda.Stream()
+        side.wait_stream(torch.cuda.current_stream())
+        with torch.cuda.stream(side):
+            binding.attention(sq, sk, sv, T, Hs, Ws, 2, True, out=sout)
+        torch.cuda.current_stream().wait_stream(side)
+        graph = torch.cuda.CUDAGraph()
+        with torch.cuda.graph(graph):
+            binding.attention(sq, sk, sv, T, Hs, Ws, 2, True, out=sout)
+        for r in (1, 2, 0, 1):
+            nq, nk, nv = dev_inputs(r)
+            sq.copy_(nq); sk.copy_(nk); sv.copy_(nv)
+            sout.fill_(float("nan"))
+            graph.replay()
+            torch.cuda.synchronize()
+            assert torch.equal(sout, eager[r])
+            # eager work of the same library between replays
+            assert torch.equal(binding.attention(nq, nk, nv, T, Hs, Ws, 2, True), eager[r])
+    finally:
+        torch.cuda.synchronize()
+        binding.set_workspace(None)
+
+
 def test_mfma_probe_runs_and_counts_its_work(env):
     torch, binding, dev = env
     blocks, iters = 4, 3
