@@ -28,14 +28,11 @@ namespace vm {
 namespace {
 
 constexpr int BK = 64;          // key rows per LDS tile
-#ifndef VM_FLASH_QT
-#define VM_FLASH_QT 1           // 32-query tiles per wave
-#endif
-#ifndef VM_FLASH_NW
-#define VM_FLASH_NW 8           // waves per workgroup
-#endif
-constexpr int QT = VM_FLASH_QT;
-constexpr int NW = VM_FLASH_NW;
+// 32-query tiles per wave.  The code is written for any QT, but two tiles (half the LDS
+// reads per MFMA) need about 300 registers per wave at d = 128 and a wave has 256 with two
+// waves per SIMD, so 1 is the only value in use.
+constexpr int QT = 1;
+constexpr int NW = 8;             // waves per workgroup
 constexpr int BQ = 32 * QT * NW;  // query rows per workgroup
 constexpr int NSLOT = 4;          // LDS tile slots per tensor
 constexpr float LOG2E = 1.4426950408889634f;
