@@ -33,6 +33,8 @@ to textbook softmax attention; separable logits give exact softmax attention
 for every iteration count; brute-force entropy against c_L and against the
 online accumulator; objective non-decreasing over half-steps and bounded by
 the sum of row log-sum-exps; sum_k c_R[k,i] = T; V == 1 gives O == 1.
+Backward (Alg. 2): central finite differences of <dO, O> + <dH, H> through
+entropy_attention in every input, rows of dS summing to zero, one-key blocks.
 No worked numeric example is printed in the paper, so no paper value pins it.
 """
 from __future__ import annotations
@@ -316,6 +318,48 @@ def flash_entropy_attention(Q, K, V, Br, Bc):
 # --------------------------------------------------------------------------
 # analytic counts (Sec. 3.2 complexity, Sec. 3.3 overhead, Sec. 4.1 sparsity)
 # --------------------------------------------------------------------------
+# --------------------------------------------------------------------------
+# App. "Backward pass of Flash-Entropy-Attention", Alg. 2 (dense form)
+# --------------------------------------------------------------------------
+def entropy_attention(Q, K, V, row_scale):
+    """One softmax block with its row entropy, from the definitions.
+
+    z[i,l] = row_scale[i] * (Q[i] . K[l]);  P = softmax_l z;  O = P V;
+    lse[i] = log sum_l exp z[i,l] (Alg. 1's L);  H[i] = -sum_l P log P.
+    Returns (O, lse, H).
+    """
+    z = (Q @ K.T) * np.asarray(row_scale, dtype=np.float64).reshape(-1, 1)
+    zmax = z.max(axis=1, keepdims=True)
+    e = np.exp(z - zmax)
+    ssum = e.sum(axis=1, keepdims=True)
+    P = e / ssum
+    lse = (zmax + np.log(ssum))[:, 0]
+    return P @ V, lse, -neg_entropy_rows(P)
+
+
+def entropy_attention_backward(Q, K, V, O, dO, lse, H, dH, row_scale):
+    """Alg. 2 without the blocking: the steps of its inner loop on whole matrices.
+
+    S is the scaled logit matrix z above.  D = rowsum(dO o O); P = exp(S - lse);
+    dV = P^T dO; dP = dO V^T; dS = P o (dP - D) - dH o P o (S - lse + H);
+    dQ = dS K and dK = dS^T Q, each carrying the row's logit scale (S = scale * Q K^T).
+    dH = None stands for all zeros (no gradient through the entropy).
+    Returns (dQ, dK, dV).
+    """
+    sc = np.asarray(row_scale, dtype=np.float64).reshape(-1, 1)
+    S = (Q @ K.T) * sc
+    D = (dO * O).sum(axis=1, keepdims=True)
+    P = np.exp(S - lse.reshape(-1, 1))
+    dV = P.T @ dO
+    dP = dO @ V.T
+    dS = P * (dP - D)
+    if dH is not None:
+        dS = dS - dH.reshape(-1, 1) * P * (S - lse.reshape(-1, 1) + H.reshape(-1, 1))
+    dQ = (dS * sc) @ K
+    dK = (dS * sc).T @ Q
+    return dQ, dK, dV
+
+
 def sparsity_estimate(T, HW, t):
     """Sec. 4.1: 1 - t (T + HW) / (T HW)."""
     return 1.0 - t * (T + HW) / (T * HW)
