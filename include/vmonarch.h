@@ -185,6 +185,33 @@ int vmonarch_permute_tokens(const void* in, void* out, int B, int heads, int T, 
                             int row_bytes, int to_position_major, void* stream);
 
 /*
+ * Backward of one blocked-softmax pass with entropy (App. "Backward pass of
+ * Flash-Entropy-Attention", Alg. 2), for the same batch of per-frame problems as
+ * vmonarch_r_update.  With, for every frame k and query position i,
+ *     z[l] = row_scale * (q[k,i,:] . K[k,l,:]) / max(cR[k,i], cr_min)    (cR == NULL: all ones)
+ *     P = softmax_l z,   O[k,i,:] = sum_l P[l] V[k,l,:],   H[k,i] = -sum_l P[l] log P[l]
+ * it returns the gradients of  <dO, O> + <dH, H>  with respect to q, K and V:
+ *     dS[i,l]  = P (dO[i].V[l] - D[i]) - dH[i] P (z[l] - lse[i] + H[i]),  D[i] = dO[i] . O[i]
+ *     dq[k,i,:] = scale_i sum_l dS[i,l] K[k,l,:]    (scale_i = row_scale / max(cR, cr_min))
+ *     dk[k,l,:] = sum_i scale_i dS[i,l] q[k,i,:]    dv[k,l,:] = sum_i P[i,l] dO[k,i,:]
+ * q, k, v, o, dO, dq_out, dk_out, dv_out: [B][heads][T][b][d]; lse, H, dH: float32 [B][heads][T][b].
+ * o, lse and H are the forward results (vmonarch_r_update_lse returns lse and cL = -H; its aL is
+ * O for V := K, its y is O for V).  dH == NULL means no gradient through the entropy, which is
+ * how the paper trains.  No gradient with respect to cR is returned.  Uses the workspace
+ * (B*heads*N floats).  Plain-ALU kernels on every shape (no MFMA path yet); results are
+ * bit-reproducible: nothing is accumulated across workgroups.
+ */
+int vmonarch_entropy_attention_bwd(const void* q, const float* cR, const void* k, const void* v, const void* o,
+                                   const void* dO, const float* lse, const float* H, const float* dH,
+                                   void* dq_out, void* dk_out, void* dv_out, int B, int heads, int T, int Hs,
+                                   int Ws, int d, float row_scale, float cr_min, void* stream);
+int vmonarch_entropy_attention_bwd_f32(const void* q, const float* cR, const void* k, const void* v,
+                                       const void* o, const void* dO, const float* lse, const float* H,
+                                       const float* dH, void* dq_out, void* dk_out, void* dv_out, int B,
+                                       int heads, int T, int Hs, int Ws, int d, float row_scale, float cr_min,
+                                       void* stream);
+
+/*
  * Benchmark aid: the sustained rate of the bf16 matrix instruction the MFMA kernels are built
  * on (v_mfma_f32_32x32x16_bf16) with nothing else running, on operand data the caller
  * supplies.  Launches `blocks` workgroups of 8 waves; every lane reads 8 x 16 bytes from

@@ -29,7 +29,8 @@ EXPORTS = [
     "vmonarch_first_frame_attention", "vmonarch_first_frame_attention_f32", "vmonarch_index_maps",
     "vmonarch_permute_tokens", "vmonarch_set_phase_timing", "vmonarch_get_phase_timing",
     "vmonarch_r_update_lse", "vmonarch_r_update_lse_f32", "vmonarch_first_frame_attention_lse",
-    "vmonarch_first_frame_attention_lse_f32", "vmonarch_mfma_probe",
+    "vmonarch_first_frame_attention_lse_f32", "vmonarch_mfma_probe", "vmonarch_entropy_attention_bwd",
+    "vmonarch_entropy_attention_bwd_f32",
 ]
 
 
@@ -71,6 +72,8 @@ def lib() -> ctypes.CDLL:
             getattr(L, name).argtypes = [c_void_p] * 7 + dims + [c_float, c_void_p]
         for name in ("vmonarch_first_frame_attention", "vmonarch_first_frame_attention_f32"):
             getattr(L, name).argtypes = [c_void_p] * 4 + dims + [c_void_p]
+        for name in ("vmonarch_entropy_attention_bwd", "vmonarch_entropy_attention_bwd_f32"):
+            getattr(L, name).argtypes = [c_void_p] * 12 + dims + [c_float, c_float, c_void_p]
         L.vmonarch_mfma_probe.argtypes = [c_void_p, c_void_p, c_int, c_int, c_void_p, c_void_p]
         L.vmonarch_index_maps.argtypes = [c_int, c_int, c_int, c_void_p, c_void_p]
         L.vmonarch_permute_tokens.argtypes = [c_void_p, c_void_p, c_int, c_int, c_int, c_int, c_int, c_int, c_int,
@@ -216,6 +219,16 @@ def first_frame_attention_lse(q, k, v, T, Hs, Ws, out):
     fn = getattr(lib(), "vmonarch_first_frame_attention_lse" + _suffix(q))
     _check(fn(_ptr(q), _ptr(k), _ptr(v), _ptr(out), _ptr(lse), B, heads, T, Hs, Ws, d, _stream()))
     return out, lse
+
+
+def entropy_attention_bwd(q, cR, k, v, o, dO, lse, H, dH, T, Hs, Ws, row_scale, cr_min):
+    """Alg. 2: returns (dq, dk, dv) for the batch of per-frame softmax blocks; dH may be None."""
+    B, heads, N, d = q.shape
+    dq, dk, dv = torch.empty_like(q), torch.empty_like(q), torch.empty_like(q)
+    fn = getattr(lib(), "vmonarch_entropy_attention_bwd" + _suffix(q))
+    _check(fn(_ptr(q), _ptr(cR), _ptr(k), _ptr(v), _ptr(o), _ptr(dO), _ptr(lse), _ptr(H), _ptr(dH), _ptr(dq), _ptr(dk),
+              _ptr(dv), B, heads, T, Hs, Ws, d, c_float(row_scale), c_float(cr_min), _stream()))
+    return dq, dk, dv
 
 
 def mfma_probe(operands, blocks, iters):

@@ -8,7 +8,7 @@ import sys
 HERE = os.path.dirname(os.path.abspath(__file__))
 CSRC = os.path.join(HERE, "csrc")
 LIB = os.path.join(HERE, "libvmonarch.so")
-SOURCES = ["api.hip", "generic.hip", "flash.hip", "lpass.hip"]
+SOURCES = ["api.hip", "generic.hip", "flash.hip", "lpass.hip", "backward.hip"]
 FLAGS = [
     "-O3", "-std=c++17", "--offload-arch=gfx950", "-fPIC", "-fvisibility=hidden",
     # keep the compiler from forming packed fp32 VALU instructions

@@ -297,6 +297,24 @@ int first_frame_impl(const void* q, const void* k, const void* v, void* out, flo
   return first_frame_any<E>((const E*)q, (const E*)k, (const E*)v, (E*)out, lse, scratch, sb, dm, (hipStream_t)stream);
 }
 
+template <typename E>
+int entropy_bwd_impl(const void* q, const float* cR, const void* k, const void* v, const void* o, const void* dO,
+                     const float* lse, const float* H, const float* dH, void* dq, void* dk, void* dv, int B, int heads,
+                     int T, int Hs, int Ws, int d, float row_scale, float cr_min, void* stream) {
+  if (!q || !k || !v || !o || !dO || !lse || !H || !dq || !dk || !dv)
+    return fail(VMONARCH_ERR_INVALID_ARG, "null tensor pointer");
+  if (!(row_scale > 0.f) || !(cr_min >= 0.f)) return fail(VMONARCH_ERR_INVALID_ARG, "row_scale must be > 0 and cr_min >= 0");
+  Dims dm;
+  int rc = make_dims(B, heads, T, Hs, Ws, d, &dm);
+  if (rc) return rc;
+  void* scratch = get_workspace(align_up(entropy_bwd_scratch_bytes(dm)), &rc);
+  if (!scratch) return rc;
+  hipError_t e = launch_entropy_bwd_generic<E>((const E*)q, cR, (const E*)k, (const E*)v, (const E*)o, (const E*)dO, lse,
+                                               H, dH, (E*)dq, (E*)dk, (E*)dv, (float*)scratch, dm, row_scale, cr_min,
+                                               (hipStream_t)stream);
+  return e == hipSuccess ? VMONARCH_OK : hip_fail(e, "entropy_attention_bwd launch");
+}
+
 }  // namespace
 
 extern "C" {
@@ -463,6 +481,21 @@ int vmonarch_permute_tokens(const void* in, void* out, int B, int heads, int T, 
   if (rc) return rc;
   hipError_t e = launch_permute_tokens(in, out, dm, row_bytes, to_position_major, (hipStream_t)stream);
   return e == hipSuccess ? VMONARCH_OK : hip_fail(e, "permute_tokens launch");
+}
+
+int vmonarch_entropy_attention_bwd(const void* q, const float* cR, const void* k, const void* v, const void* o,
+                                   const void* dO, const float* lse, const float* H, const float* dH, void* dq_out,
+                                   void* dk_out, void* dv_out, int B, int heads, int T, int Hs, int Ws, int d,
+                                   float row_scale, float cr_min, void* stream) {
+  return entropy_bwd_impl<bf16_t>(q, cR, k, v, o, dO, lse, H, dH, dq_out, dk_out, dv_out, B, heads, T, Hs, Ws, d,
+                                  row_scale, cr_min, stream);
+}
+int vmonarch_entropy_attention_bwd_f32(const void* q, const float* cR, const void* k, const void* v, const void* o,
+                                       const void* dO, const float* lse, const float* H, const float* dH,
+                                       void* dq_out, void* dk_out, void* dv_out, int B, int heads, int T, int Hs,
+                                       int Ws, int d, float row_scale, float cr_min, void* stream) {
+  return entropy_bwd_impl<float>(q, cR, k, v, o, dO, lse, H, dH, dq_out, dk_out, dv_out, B, heads, T, Hs, Ws, d,
+                                 row_scale, cr_min, stream);
 }
 
 int vmonarch_mfma_probe(const void* operands, float* out, int blocks, int iters, double* flops_host, void* stream) {

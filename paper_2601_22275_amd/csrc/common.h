@@ -80,6 +80,13 @@ hipError_t launch_first_frame_generic(const E* q, const E* k, const E* v, E* out
 hipError_t launch_permute_tokens(const void* in, void* out, const Dims& dm, int row_bytes, int to_pos_major,
                                  hipStream_t st);
 
+// backward.hip : Alg. 2 on the plain ALUs (D_scratch: BH * N floats)
+size_t entropy_bwd_scratch_bytes(const Dims& dm);
+template <typename E>
+hipError_t launch_entropy_bwd_generic(const E* q, const float* cR, const E* k, const E* v, const E* o, const E* dO,
+                                      const float* lse, const float* H, const float* dH, E* dq, E* dk, E* dv,
+                                      float* D_scratch, const Dims& dm, float row_scale, float cr_min, hipStream_t st);
+
 hipError_t launch_mfma_probe(const void* operands, float* out, int blocks, int iters, hipStream_t st);
 
 // flash.hip : bf16 MFMA blocked-softmax kernels (d == 64 or 128)

@@ -1,0 +1,78 @@
+"""GPU parity of the Alg. 2 backward (through the C ABI) against the CPU oracle."""
+import math
+
+import numpy as np
+import pytest
+
+from oracle import vmonarch_oracle as O
+from tests import util as U
+
+pytestmark = pytest.mark.gpu
+
+
+@pytest.fixture(scope="module")
+def env():
+    import torch
+    from paper_2601_22275_amd import binding
+    assert torch.cuda.is_available()
+    binding.lib()
+    return torch, binding, torch.device("cuda:0")
+
+
+CASES = [
+    # T, Hs, Ws, d, dtype, with_dH, with_cR
+    (2, 3, 5, 8, "f32", True, True),
+    (3, 4, 4, 32, "f32", False, False),
+    (1, 9, 11, 20, "f32", True, False),     # b = 99: two key chunks, ragged
+    (2, 1, 1, 16, "f32", True, True),       # one key: no logit gradient
+    (2, 8, 9, 64, "bf16", True, True),
+    (1, 13, 10, 128, "bf16", False, True),  # b = 130
+]
+
+
+@pytest.mark.parametrize("T,Hs,Ws,d,dt,with_dh,with_cr", CASES)
+def test_entropy_attention_backward_matches_oracle(env, T, Hs, Ws, d, dt, with_dh, with_cr):
+    torch, binding, dev = env
+    bf16 = dt == "bf16"
+    b, heads = Hs * Ws, 2
+    N = T * b
+    rng = np.random.default_rng(500 + T * 31 + b)
+    data = U.structured_heads(T, Hs, Ws, d, 21, heads, bf16)
+    Q = [h[0] for h in data]; K = [h[1] for h in data]; V = [h[2] for h in data]
+    dO = [U.random_bits(rng, (N, d), 1.0, bf16) for _ in range(heads)]
+    cR = (0.3 + 1.5 * rng.random((heads, N))).astype(np.float32) if with_cr else None
+    dH = rng.normal(size=(heads, N)).astype(np.float32) if with_dh else None
+    row_scale, cr_min = 1.0 / math.sqrt(d), 0.1
+    tq, tk, tv, tdo = (U.to_device(x, torch, dev) for x in (Q, K, V, dO))
+    tcr = torch.from_numpy(cR).to(dev).view(1, heads, N) if with_cr else None
+    tdh = torch.from_numpy(dH).to(dev).view(1, heads, N) if with_dh else None
+    # forward results from the library itself: O = y (values V), lse, H = -cL
+    _, cL, y, lse = binding.r_update_lse(tq, tcr, tk, tv, T, Hs, Ws, row_scale, cr_min)
+    Hent = (-cL).contiguous()
+    dq, dk, dv = binding.entropy_attention_bwd(tq, tcr, tk, tv, y, tdo, lse, Hent, tdh, T, Hs, Ws, row_scale, cr_min)
+    again = binding.entropy_attention_bwd(tq, tcr, tk, tv, y, tdo, lse, Hent, tdh, T, Hs, Ws, row_scale, cr_min)
+    assert all(torch.equal(a, c) for a, c in zip((dq, dk, dv), again))     # bit-reproducible
+    gdq, gdk, gdv = (U.from_device(x) for x in (dq, dk, dv))
+    rel_tol = 2e-2 if bf16 else 2e-4
+    for h in range(heads):
+        q64, k64, v64, do64 = (U.to_f64(x[h]).reshape(T, b, d) for x in (Q, K, V, dO))
+        for kf in range(T):
+            c = np.maximum(cR[h].reshape(T, b)[kf].astype(np.float64), cr_min) if with_cr else np.ones(b)
+            sc = row_scale / c
+            Oo, l64, H64 = O.entropy_attention(q64[kf], k64[kf], v64[kf], sc)
+            dh64 = dH[h].reshape(T, b)[kf].astype(np.float64) if with_dh else None
+            rdq, rdk, rdv = O.entropy_attention_backward(q64[kf], k64[kf], v64[kf], Oo, do64[kf], l64, H64, dh64, sc)
+            for name, got, ref in (("dq", gdq, rdq), ("dk", gdk, rdk), ("dv", gdv, rdv)):
+                g = got[h].reshape(T, b, d)[kf]
+                err = U.rel_l2(g, ref) if np.abs(ref).max() > 0 else float(np.abs(g).max())
+                if kf == 0:
+                    print(f"bwd T={T} b={b} d={d} {dt} dH={with_dh} head {h} {name}: rel {err:.2e} |ref| {np.abs(ref).max():.2e}")
+                assert err <= rel_tol, (name, err)
+
+
+def test_backward_rejects_bad_arguments(env):
+    torch, binding, dev = env
+    x = torch.zeros(1, 1, 4, 8, device=dev)
+    s = torch.zeros(1, 1, 4, device=dev)
+    with pytest.raises(binding.VMonarchError):
+        binding.entropy_attention_bwd(x, None, x, x, x, x, s, s, None, 2, 1, 2, -1.0, 0.1)
