@@ -107,6 +107,28 @@ def test_r_update_matches_oracle(env, T, Hs, Ws, d, dt, with_v, with_cr, mode):
             assert U.rel_l2(gy, ref_y) <= rel_tol and U.max_abs(gy, ref_y) <= abs_tol
 
 
+@pytest.mark.parametrize("d", [64, 128])
+@pytest.mark.parametrize("b", [31, 32, 33, 63, 64, 65, 95, 96, 97, 127, 128, 129, 191, 255, 256, 257, 320, 511, 513])
+def test_r_update_at_every_tile_boundary(env, b, d):
+    """One frame of b tokens around every boundary of the blocked kernel: 32-key sub-tiles, 64-key tiles,
+    32-row waves, 256-row query blocks, the four-tile LDS rotation."""
+    torch, binding, dev = env
+    rng = np.random.default_rng(9000 + 7 * b + d)
+    q = U.random_bits(rng, (b, d), 1.2, True)
+    k = U.random_bits(rng, (b, d), 1.2, True)
+    v = U.random_bits(rng, (b, d), 1.0, True)
+    cR = (0.2 + 2.0 * rng.random((1, b))).astype(np.float32)
+    row_scale, cr_min = 1.0 / math.sqrt(d), 0.1
+    tq, tk, tv = (U.to_device([x], torch, dev) for x in (q, k, v))
+    aL, cL, y = binding.r_update(tq, torch.from_numpy(cR).to(dev).view(1, 1, -1), tk, tv, 1, 1, b, row_scale, cr_min)
+    z = (U.to_f64(q) @ U.to_f64(k).T) * row_scale / np.maximum(cR[0].astype(np.float64), cr_min).reshape(-1, 1)
+    R = O.softmax_rows(z)
+    for name, got, ref in (("aL", aL, R @ U.to_f64(k)), ("y", y, R @ U.to_f64(v))):
+        g = U.from_device(got)[0]
+        assert U.rel_l2(g, ref) <= U.BF16_REL_L2 and U.max_abs(g, ref) <= U.BF16_MAX_ABS, (name, b, d)
+    assert U.max_abs(U.from_device(cL)[0], O.neg_entropy_rows(R)) <= 2e-2
+
+
 @pytest.mark.parametrize("T,Hs,Ws,d,dt", [(4, 4, 4, 32, "f32"), (3, 10, 30, 128, "bf16"), (2, 3, 11, 64, "bf16"),
                                            (2, 9, 9, 96, "bf16")])
 def test_r_update_log_sum_exp_output(env, T, Hs, Ws, d, dt):
@@ -210,6 +232,22 @@ def test_first_frame_attention_matches_oracle(env, T, Hs, Ws, d, dt):
         print(f"first_frame T={T} b={b} d={d} {dt}: rel {U.rel_l2(got[h][:b], ref):.2e} max {U.max_abs(got[h][:b], ref):.2e}")
         assert U.rel_l2(got[h][:b], ref) <= rel_tol and U.max_abs(got[h][:b], ref) <= abs_tol
         assert (got[h][b:] == 7.0).all()          # nothing beyond frame 0 is written
+
+
+@pytest.mark.parametrize("T,b", [(15, 64), (16, 64), (17, 64), (33, 40), (64, 33), (130, 31), (9, 300)])
+def test_first_frame_key_range_splits(env, T, b):
+    """N = T b keys around the points where the pass starts splitting the key range (at least 8 tiles per
+    range) and where ranges end in ragged tiles."""
+    torch, binding, dev = env
+    d = 128
+    rng = np.random.default_rng(700 + T * b)
+    q, k, v = (U.random_bits(rng, (T * b, d), s, True) for s in (1.2, 1.2, 1.0))
+    tq, tk, tv = (U.to_device([x], torch, dev) for x in (q, k, v))
+    out = torch.zeros_like(tq)
+    binding.first_frame_attention(tq, tk, tv, T, 1, b, out)
+    ref = O.first_frame_attention(U.to_f64(q), U.to_f64(k), U.to_f64(v), b)
+    g = U.from_device(out)[0][:b]
+    assert U.rel_l2(g, ref) <= U.BF16_REL_L2 and U.max_abs(g, ref) <= U.BF16_MAX_ABS
 
 
 @pytest.mark.parametrize("T,Hs,Ws,d,dt", [(4, 4, 4, 32, "f32"), (1, 3, 3, 128, "bf16"), (9, 7, 9, 128, "bf16"),
