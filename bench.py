@@ -144,6 +144,50 @@ def sweep_frames(args) -> int:
     return 0
 
 
+def bench_backward(args) -> int:
+    """Backward of one blocked-softmax pass with entropy (Alg. 2) on the workload's per-frame problems:
+    dq, dk, dv for every (head, frame) from K, V, the forward outputs and seeded random dO, dH.  One JSON
+    line; FLOPs counted as Alg. 2's five b x b x d products per problem (the three passes issue eight)."""
+    import numpy as np
+    import torch
+
+    from paper_2601_22275_amd import binding, synth
+
+    dev = torch.device("cuda:0")
+    binding.lib()
+    wl = synth.WORKLOADS[args.workload]
+    q, k, v = synth.make_inputs(wl)
+    tq, tk, tv = (torch.from_numpy(x).to(dev).view(torch.bfloat16).view(wl.B, wl.heads, wl.N, wl.d) for x in (q, k, v))
+    g = torch.Generator(device="cpu")
+    g.manual_seed(3)
+    dO = torch.randn(wl.B, wl.heads, wl.N, wl.d, generator=g).to(torch.bfloat16).to(dev)
+    dH = torch.randn(wl.B, wl.heads, wl.N, generator=g).to(dev)
+    s = 1.0 / math.sqrt(wl.d)
+    _, cL, y, lse = binding.r_update_lse(tq, None, tk, tv, wl.T, wl.Hs, wl.Ws, s, 0.1)
+    H = (-cL).contiguous()
+
+    def step():
+        return binding.entropy_attention_bwd(tq, None, tk, tv, y, dO, lse, H, dH, wl.T, wl.Hs, wl.Ws, s, 0.1)
+
+    for _ in range(args.warmup):
+        step()
+    torch.cuda.synchronize()
+    e0, e1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+    e0.record()
+    for _ in range(args.steps):
+        step()
+    e1.record()
+    torch.cuda.synchronize()
+    ms = e0.elapsed_time(e1) / args.steps
+    fl = 10.0 * wl.B * wl.heads * wl.T * wl.b * wl.b * wl.d
+    print(json.dumps({"metric": "Alg. 2 backward of the blocked-softmax pass, TFLOP/s (five products per problem / time)",
+                      "value": fl / ms / 1e9, "unit": "TFLOP/s", "n_gpus": 1, "steps": args.steps, "warmup": args.warmup,
+                      "ms_per_step": ms, "higher_is_better": True, "scaling": "weak", "vs_baseline": None,
+                      "dtype": "bf16", "data": "synthetic", "issued_tflops": 1.6 * fl / ms / 1e9,
+                      "config": {"workload": wl.name, "heads": wl.heads, "T": wl.T, "b": wl.b, "d": wl.d}}))
+    return 0
+
+
 def main() -> int:
     ap = argparse.ArgumentParser()
     ap.add_argument("--gpus", type=int, default=1)
@@ -154,6 +198,8 @@ def main() -> int:
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--copy-calibration", action="store_true",
                     help="also run one token-permutation copy of known size (reference for HBM byte counters)")
+    ap.add_argument("--backward", action="store_true",
+                    help="time the Alg. 2 backward of the workload's per-frame softmax blocks instead of the forward path")
     ap.add_argument("--graph", action="store_true",
                     help="capture one call in a HIP graph and time replays (for launch-bound small workloads)")
     ap.add_argument("--sweep-frames", action="store_true",
@@ -173,6 +219,8 @@ def main() -> int:
         return 2
     if args.sweep_frames:
         return sweep_frames(args)
+    if args.backward:
+        return bench_backward(args)
     binding.lib()  # fail loudly when the HIP library is missing
     wl = synth.WORKLOADS[args.workload]
     dev = torch.device("cuda:0")

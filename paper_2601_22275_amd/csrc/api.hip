@@ -307,8 +307,15 @@ int entropy_bwd_impl(const void* q, const float* cR, const void* k, const void* 
   Dims dm;
   int rc = make_dims(B, heads, T, Hs, Ws, d, &dm);
   if (rc) return rc;
-  void* scratch = get_workspace(align_up(entropy_bwd_scratch_bytes(dm)), &rc);
+  const bool mfma = sizeof(E) == 2 && entropy_bwd_mfma_supported(dm);
+  void* scratch = get_workspace(align_up(mfma ? entropy_bwd_mfma_scratch_bytes(dm) : entropy_bwd_scratch_bytes(dm)), &rc);
   if (!scratch) return rc;
+  if (mfma) {
+    hipError_t e = launch_entropy_bwd_mfma((const bf16_t*)q, cR, (const bf16_t*)k, (const bf16_t*)v, (const bf16_t*)o,
+                                           (const bf16_t*)dO, lse, H, dH, (bf16_t*)dq, (bf16_t*)dk, (bf16_t*)dv, scratch,
+                                           dm, row_scale, cr_min, (hipStream_t)stream);
+    return e == hipSuccess ? VMONARCH_OK : hip_fail(e, "entropy_attention_bwd (MFMA) launch");
+  }
   hipError_t e = launch_entropy_bwd_generic<E>((const E*)q, cR, (const E*)k, (const E*)v, (const E*)o, (const E*)dO, lse,
                                                H, dH, (E*)dq, (E*)dk, (E*)dv, (float*)scratch, dm, row_scale, cr_min,
                                                (hipStream_t)stream);

@@ -87,6 +87,14 @@ hipError_t launch_entropy_bwd_generic(const E* q, const float* cR, const E* k, c
                                       const float* lse, const float* H, const float* dH, E* dq, E* dk, E* dv,
                                       float* D_scratch, const Dims& dm, float row_scale, float cr_min, hipStream_t st);
 
+// backward_mfma.hip : Alg. 2 on the MFMA units (bf16, d == 64 or 128; scratch: one float4 per query row)
+bool entropy_bwd_mfma_supported(const Dims& dm);
+size_t entropy_bwd_mfma_scratch_bytes(const Dims& dm);
+hipError_t launch_entropy_bwd_mfma(const bf16_t* q, const float* cR, const bf16_t* k, const bf16_t* v,
+                                   const bf16_t* o, const bf16_t* dO, const float* lse, const float* H,
+                                   const float* dH, bf16_t* dq, bf16_t* dk, bf16_t* dv, void* scratch, const Dims& dm,
+                                   float row_scale, float cr_min, hipStream_t st);
+
 hipError_t launch_mfma_probe(const void* operands, float* out, int blocks, int iters, hipStream_t st);
 
 // flash.hip : bf16 MFMA blocked-softmax kernels (d == 64 or 128)

@@ -25,8 +25,13 @@ CASES = [
     (3, 4, 4, 32, "f32", False, False),
     (1, 9, 11, 20, "f32", True, False),     # b = 99: two key chunks, ragged
     (2, 1, 1, 16, "f32", True, True),       # one key: no logit gradient
-    (2, 8, 9, 64, "bf16", True, True),
-    (1, 13, 10, 128, "bf16", False, True),  # b = 130
+    (2, 8, 9, 96, "bf16", True, True),      # plain-ALU bf16 (d not 64 or 128)
+    (2, 8, 9, 64, "bf16", True, True),      # MFMA, d = 64
+    (1, 13, 10, 128, "bf16", False, True),  # MFMA, b = 130
+    (2, 10, 30, 128, "bf16", True, True),   # b = 300: two owner blocks, ragged last stream tile
+    (1, 23, 29, 64, "bf16", True, False),   # b = 667
+    (2, 1, 1, 128, "bf16", True, True),     # one key
+    (1, 4, 8, 128, "bf16", True, True),     # b = 32: exactly one sub-tile
 ]
 
 
@@ -53,18 +58,24 @@ def test_entropy_attention_backward_matches_oracle(env, T, Hs, Ws, d, dt, with_d
     again = binding.entropy_attention_bwd(tq, tcr, tk, tv, y, tdo, lse, Hent, tdh, T, Hs, Ws, row_scale, cr_min)
     assert all(torch.equal(a, c) for a, c in zip((dq, dk, dv), again))     # bit-reproducible
     gdq, gdk, gdv = (U.from_device(x) for x in (dq, dk, dv))
-    rel_tol = 2e-2 if bf16 else 2e-4
+    # Alg. 2 takes O, L and H as inputs: the oracle gets the very values the kernel was given
+    # (the forward pass's rounded outputs), so that the comparison isolates the backward arithmetic
+    gy, glse, gH = U.from_device(y), U.from_device(lse), U.from_device(Hent)
+    rel_tol = 1e-2 if bf16 else 2e-4
     for h in range(heads):
         q64, k64, v64, do64 = (U.to_f64(x[h]).reshape(T, b, d) for x in (Q, K, V, dO))
         for kf in range(T):
             c = np.maximum(cR[h].reshape(T, b)[kf].astype(np.float64), cr_min) if with_cr else np.ones(b)
             sc = row_scale / c
-            Oo, l64, H64 = O.entropy_attention(q64[kf], k64[kf], v64[kf], sc)
+            Oo = gy[h].reshape(T, b, d)[kf].astype(np.float64)
+            l64 = glse[h].reshape(T, b)[kf].astype(np.float64)
+            H64 = gH[h].reshape(T, b)[kf].astype(np.float64)
             dh64 = dH[h].reshape(T, b)[kf].astype(np.float64) if with_dh else None
             rdq, rdk, rdv = O.entropy_attention_backward(q64[kf], k64[kf], v64[kf], Oo, do64[kf], l64, H64, dh64, sc)
             for name, got, ref in (("dq", gdq, rdq), ("dk", gdk, rdk), ("dv", gdv, rdv)):
                 g = got[h].reshape(T, b, d)[kf]
-                err = U.rel_l2(g, ref) if np.abs(ref).max() > 0 else float(np.abs(g).max())
+                # one-key blocks have no logit gradient: both sides hold rounding noise only
+                err = U.rel_l2(g, ref) if np.abs(ref).max() > 1e-4 else float(np.abs(g - ref).max()) * (rel_tol / 1e-5)
                 if kf == 0:
                     print(f"bwd T={T} b={b} d={d} {dt} dH={with_dh} head {h} {name}: rel {err:.2e} |ref| {np.abs(ref).max():.2e}")
                 assert err <= rel_tol, (name, err)

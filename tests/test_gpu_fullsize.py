@@ -102,3 +102,35 @@ def test_headline_unclamped_cr_sums_to_frame_count(env):
     assert float((tot - wl.T).abs().max()) <= 5e-3 * wl.T
     assert float(cL.max()) <= 1e-4          # c_L = -entropy <= 0
     assert float(cL.min()) >= -math.log(wl.b) - 1e-3
+
+
+def test_backward_at_headline_shape_sampled_frames(env):
+    """Alg. 2 backward on the 81 x 28 x 52 shape (one head, all 81 frames computed); three frames are checked
+    entirely against the oracle, which is fed the kernel's own forward inputs."""
+    torch, binding, dev = env
+    wl = synth.WORKLOADS["long-81x28x52"]
+    q, k, v = synth.make_inputs(wl, heads=[4])
+    rng = np.random.default_rng(11)
+    dO = U.random_bits(rng, (wl.N, wl.d), 1.0, True)
+    dH = rng.normal(size=wl.N).astype(np.float32)
+    tq, tk, tv = (torch.from_numpy(x).to(dev).view(torch.bfloat16).view(1, 1, wl.N, wl.d) for x in (q, k, v))
+    tdo = U.to_device([dO], torch, dev)
+    tdh = torch.from_numpy(dH).to(dev).view(1, 1, -1)
+    s = 1.0 / math.sqrt(wl.d)
+    _, cL, y, lse = binding.r_update_lse(tq, None, tk, tv, wl.T, wl.Hs, wl.Ws, s, 0.1)
+    Hent = (-cL).contiguous()
+    dq, dk, dv = binding.entropy_attention_bwd(tq, None, tk, tv, y, tdo, lse, Hent, tdh, wl.T, wl.Hs, wl.Ws, s, 0.1)
+    assert all(bool(torch.isfinite(x.float()).all()) for x in (dq, dk, dv))
+    got = [U.from_device(x)[0].reshape(wl.T, wl.b, wl.d) for x in (dq, dk, dv)]
+    gy, glse, gH = (U.from_device(x)[0] for x in (y, lse, Hent))
+    q64, k64, v64 = (O.widen_bf16(x[0]).reshape(wl.T, wl.b, wl.d) for x in (q, k, v))
+    do64 = U.to_f64(dO).reshape(wl.T, wl.b, wl.d)
+    for kf in (0, 37, 80):
+        ref = O.entropy_attention_backward(q64[kf], k64[kf], v64[kf], gy.reshape(wl.T, wl.b, wl.d)[kf].astype(np.float64),
+                                           do64[kf], glse.reshape(wl.T, wl.b)[kf].astype(np.float64),
+                                           gH.reshape(wl.T, wl.b)[kf].astype(np.float64),
+                                           dH.reshape(wl.T, wl.b)[kf].astype(np.float64), np.full(wl.b, s))
+        for name, g, r in zip(("dq", "dk", "dv"), got, ref):
+            err = U.rel_l2(g[kf], r)
+            print(f"backward frame {kf} {name}: rel {err:.2e}")
+            assert err <= 1e-2
