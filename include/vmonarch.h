@@ -169,6 +169,19 @@ int vmonarch_first_frame_attention_lse_f32(const void* q, const void* k, const v
                                            int d, void* stream);
 
 /*
+ * Recomputation of an arbitrary contiguous range of tokens (Sec. 3.3 names the first frame;
+ * the strategy applies to any tokens): out[row_begin : row_begin + row_count] of every head =
+ * softmax(Q[rows] K^T / sqrt(d)) V over all N keys.  Only those rows of `out` are written.
+ * 0 <= row_begin, 1 <= row_count, row_begin + row_count <= N.  The first-frame call is
+ * row_begin = 0, row_count = Hs*Ws.
+ */
+int vmonarch_recompute_rows(const void* q, const void* k, const void* v, void* out, int B, int heads, int T,
+                            int Hs, int Ws, int d, long long row_begin, long long row_count, void* stream);
+int vmonarch_recompute_rows_f32(const void* q, const void* k, const void* v, void* out, int B, int heads,
+                                int T, int Hs, int Ws, int d, long long row_begin, long long row_count,
+                                void* stream);
+
+/*
  * Permutation P_(b,N) of Sec. 3.1 (its footnote: reshape to m x b, transpose, flatten).
  * perm, inv: HOST int32[N]; position-major slot p = i*T + j holds token perm[p] = j*b + i,
  * and inv[j*b + i] = i*T + j.

@@ -30,7 +30,7 @@ EXPORTS = [
     "vmonarch_permute_tokens", "vmonarch_set_phase_timing", "vmonarch_get_phase_timing",
     "vmonarch_r_update_lse", "vmonarch_r_update_lse_f32", "vmonarch_first_frame_attention_lse",
     "vmonarch_first_frame_attention_lse_f32", "vmonarch_mfma_probe", "vmonarch_entropy_attention_bwd",
-    "vmonarch_entropy_attention_bwd_f32",
+    "vmonarch_entropy_attention_bwd_f32", "vmonarch_recompute_rows", "vmonarch_recompute_rows_f32",
 ]
 
 
@@ -74,6 +74,8 @@ def lib() -> ctypes.CDLL:
             getattr(L, name).argtypes = [c_void_p] * 4 + dims + [c_void_p]
         for name in ("vmonarch_entropy_attention_bwd", "vmonarch_entropy_attention_bwd_f32"):
             getattr(L, name).argtypes = [c_void_p] * 12 + dims + [c_float, c_float, c_void_p]
+        for name in ("vmonarch_recompute_rows", "vmonarch_recompute_rows_f32"):
+            getattr(L, name).argtypes = [c_void_p] * 4 + dims + [ctypes.c_longlong, ctypes.c_longlong, c_void_p]
         L.vmonarch_mfma_probe.argtypes = [c_void_p, c_void_p, c_int, c_int, c_void_p, c_void_p]
         L.vmonarch_index_maps.argtypes = [c_int, c_int, c_int, c_void_p, c_void_p]
         L.vmonarch_permute_tokens.argtypes = [c_void_p, c_void_p, c_int, c_int, c_int, c_int, c_int, c_int, c_int,
@@ -209,6 +211,14 @@ def first_frame_attention(q, k, v, T, Hs, Ws, out):
     B, heads, N, d = q.shape
     fn = getattr(lib(), "vmonarch_first_frame_attention" + _suffix(q))
     _check(fn(_ptr(q), _ptr(k), _ptr(v), _ptr(out), B, heads, T, Hs, Ws, d, _stream()))
+    return out
+
+
+def recompute_rows(q, k, v, T, Hs, Ws, out, row_begin, row_count):
+    """Overwrites rows [row_begin, row_begin + row_count) of every head of `out` with exact attention over all keys."""
+    B, heads, N, d = q.shape
+    fn = getattr(lib(), "vmonarch_recompute_rows" + _suffix(q))
+    _check(fn(_ptr(q), _ptr(k), _ptr(v), _ptr(out), B, heads, T, Hs, Ws, d, row_begin, row_count, _stream()))
     return out
 
 

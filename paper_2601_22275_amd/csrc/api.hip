@@ -99,7 +99,7 @@ WsLayout ws_layout(const Dims& dm, int iters, int recompute, int elem_bytes) {
   w.aR = off; if (iters > 1) off += tok;
   w.cR = off; if (iters > 1) off += sc;
   w.ff = off;
-  if (recompute && elem_bytes == 2 && flash_supported(dm)) off += align_up(first_frame_flash_scratch_bytes(dm));
+  if (recompute && elem_bytes == 2 && flash_supported(dm)) off += align_up(first_frame_flash_scratch_bytes(dm, dm.b));
   w.total = off;
   return w;
 }
@@ -185,21 +185,21 @@ int l_update_any<bf16_t>(const bf16_t* q, const bf16_t* aL, const float* cL, con
 
 template <typename E>
 int first_frame_any(const E* q, const E* k, const E* v, E* out, float* lse, void* scratch, size_t scratch_bytes,
-                    const Dims& dm, hipStream_t st);
+                    const Dims& dm, int nrows, hipStream_t st);
 template <>
 int first_frame_any<float>(const float* q, const float* k, const float* v, float* out, float* lse, void*, size_t,
-                           const Dims& dm, hipStream_t st) {
-  hipError_t e = launch_first_frame_generic<float>(q, k, v, out, lse, dm, st);
+                           const Dims& dm, int nrows, hipStream_t st) {
+  hipError_t e = launch_first_frame_generic<float>(q, k, v, out, lse, dm, nrows, st);
   return e == hipSuccess ? VMONARCH_OK : hip_fail(e, "first_frame (plain-ALU f32) launch");
 }
 template <>
 int first_frame_any<bf16_t>(const bf16_t* q, const bf16_t* k, const bf16_t* v, bf16_t* out, float* lse, void* scratch,
-                            size_t scratch_bytes, const Dims& dm, hipStream_t st) {
+                            size_t scratch_bytes, const Dims& dm, int nrows, hipStream_t st) {
   hipError_t e;
   if (flash_supported(dm))
-    e = launch_first_frame_flash(q, k, v, out, lse, scratch, scratch_bytes, dm, st);
+    e = launch_first_frame_flash(q, k, v, out, lse, scratch, scratch_bytes, dm, nrows, st);
   else
-    e = launch_first_frame_generic<bf16_t>(q, k, v, out, lse, dm, st);
+    e = launch_first_frame_generic<bf16_t>(q, k, v, out, lse, dm, nrows, st);
   return e == hipSuccess ? VMONARCH_OK : hip_fail(e, "first_frame (bf16) launch");
 }
 
@@ -243,7 +243,7 @@ int attention_impl(const void* q_, const void* k_, const void* v_, void* out_, i
   }
   if (recompute) {
     phase_mark(st, "first_frame");
-    rc = first_frame_any<E>(q, k, v, out, nullptr, ws + w.ff, w.total - w.ff, dm, st);
+    rc = first_frame_any<E>(q, k, v, out, nullptr, ws + w.ff, w.total - w.ff, dm, dm.b, st);
     if (rc) return rc;
   }
   phase_mark(st, nullptr);
@@ -280,21 +280,28 @@ int l_update_impl(const void* q, const void* aL, const float* cL, const void* y,
 
 template <typename E>
 int first_frame_impl(const void* q, const void* k, const void* v, void* out, float* lse, int B, int heads, int T,
-                     int Hs, int Ws, int d, void* stream) {
+                     int Hs, int Ws, int d, long long row_begin, long long row_count, void* stream) {
   if (!q || !k || !v || !out) return fail(VMONARCH_ERR_INVALID_ARG, "null tensor pointer");
   Dims dm;
   int rc = make_dims(B, heads, T, Hs, Ws, d, &dm);
   if (rc) return rc;
+  if (row_count < 0) row_count = dm.b;  // the first frame
+  if (row_begin < 0 || row_count < 1 || row_begin + row_count > dm.N)
+    return fail(VMONARCH_ERR_INVALID_ARG, "rows [%lld, %lld) do not lie inside the %lld tokens of a head", row_begin,
+                row_begin + row_count, dm.N);
+  const int nrows = (int)row_count;
   void* scratch = nullptr;
   size_t sb = 0;
   if (sizeof(E) == 2 && flash_supported(dm)) {
-    sb = align_up(first_frame_flash_scratch_bytes(dm));
+    sb = align_up(first_frame_flash_scratch_bytes(dm, nrows));
     if (sb > 0) {
       scratch = get_workspace(sb, &rc);
       if (!scratch) return rc;
     }
   }
-  return first_frame_any<E>((const E*)q, (const E*)k, (const E*)v, (E*)out, lse, scratch, sb, dm, (hipStream_t)stream);
+  // the kernels index query rows from the pointers they are given: hand them the first row of the range
+  return first_frame_any<E>((const E*)q + row_begin * d, (const E*)k, (const E*)v, (E*)out + row_begin * d,
+                            lse ? lse + row_begin : nullptr, scratch, sb, dm, nrows, (hipStream_t)stream);
 }
 
 template <typename E>
@@ -449,21 +456,32 @@ int vmonarch_l_update_f32(const void* q, const void* aL, const float* cL, const 
 
 int vmonarch_first_frame_attention(const void* q, const void* k, const void* v, void* out, int B, int heads, int T,
                                    int Hs, int Ws, int d, void* stream) {
-  return first_frame_impl<bf16_t>(q, k, v, out, nullptr, B, heads, T, Hs, Ws, d, stream);
+  return first_frame_impl<bf16_t>(q, k, v, out, nullptr, B, heads, T, Hs, Ws, d, 0, -1, stream);
 }
 int vmonarch_first_frame_attention_f32(const void* q, const void* k, const void* v, void* out, int B, int heads, int T,
                                        int Hs, int Ws, int d, void* stream) {
-  return first_frame_impl<float>(q, k, v, out, nullptr, B, heads, T, Hs, Ws, d, stream);
+  return first_frame_impl<float>(q, k, v, out, nullptr, B, heads, T, Hs, Ws, d, 0, -1, stream);
 }
 int vmonarch_first_frame_attention_lse(const void* q, const void* k, const void* v, void* out, float* lse_out, int B,
                                        int heads, int T, int Hs, int Ws, int d, void* stream) {
   if (!lse_out) return fail(VMONARCH_ERR_INVALID_ARG, "null lse_out");
-  return first_frame_impl<bf16_t>(q, k, v, out, lse_out, B, heads, T, Hs, Ws, d, stream);
+  return first_frame_impl<bf16_t>(q, k, v, out, lse_out, B, heads, T, Hs, Ws, d, 0, -1, stream);
 }
 int vmonarch_first_frame_attention_lse_f32(const void* q, const void* k, const void* v, void* out, float* lse_out,
                                            int B, int heads, int T, int Hs, int Ws, int d, void* stream) {
   if (!lse_out) return fail(VMONARCH_ERR_INVALID_ARG, "null lse_out");
-  return first_frame_impl<float>(q, k, v, out, lse_out, B, heads, T, Hs, Ws, d, stream);
+  return first_frame_impl<float>(q, k, v, out, lse_out, B, heads, T, Hs, Ws, d, 0, -1, stream);
+}
+
+int vmonarch_recompute_rows(const void* q, const void* k, const void* v, void* out, int B, int heads, int T, int Hs,
+                            int Ws, int d, long long row_begin, long long row_count, void* stream) {
+  if (row_count < 1) return fail(VMONARCH_ERR_INVALID_ARG, "row_count must be positive");
+  return first_frame_impl<bf16_t>(q, k, v, out, nullptr, B, heads, T, Hs, Ws, d, row_begin, row_count, stream);
+}
+int vmonarch_recompute_rows_f32(const void* q, const void* k, const void* v, void* out, int B, int heads, int T, int Hs,
+                                int Ws, int d, long long row_begin, long long row_count, void* stream) {
+  if (row_count < 1) return fail(VMONARCH_ERR_INVALID_ARG, "row_count must be positive");
+  return first_frame_impl<float>(q, k, v, out, nullptr, B, heads, T, Hs, Ws, d, row_begin, row_count, stream);
 }
 
 int vmonarch_index_maps(int T, int Hs, int Ws, int32_t* perm_host, int32_t* inv_host) {

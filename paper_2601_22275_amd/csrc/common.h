@@ -76,7 +76,7 @@ hipError_t launch_l_update_generic(const E* q, const E* aL, const float* cL, con
                                    E* out, const Dims& dm, float q_scale, hipStream_t st);
 template <typename E>
 hipError_t launch_first_frame_generic(const E* q, const E* k, const E* v, E* out, float* lse, const Dims& dm,
-                                      hipStream_t st);
+                                      int nrows, hipStream_t st);
 hipError_t launch_permute_tokens(const void* in, void* out, const Dims& dm, int row_bytes, int to_pos_major,
                                  hipStream_t st);
 
@@ -103,9 +103,10 @@ bool flash_supported(const Dims& dm);
 hipError_t launch_r_update_flash(const bf16_t* aR, const float* cR, const bf16_t* k, const bf16_t* v, bf16_t* aL,
                                  float* cL, bf16_t* y, float* lse, const Dims& dm, float row_scale, float cr_min,
                                  int entropy_mode, hipStream_t st);
-size_t first_frame_flash_scratch_bytes(const Dims& dm);
+// exact attention of nrows query rows per head (starting where q / out / lse point) over all N keys
+size_t first_frame_flash_scratch_bytes(const Dims& dm, int nrows);
 hipError_t launch_first_frame_flash(const bf16_t* q, const bf16_t* k, const bf16_t* v, bf16_t* out, float* lse,
-                                    void* scratch, size_t scratch_bytes, const Dims& dm, hipStream_t st);
+                                    void* scratch, size_t scratch_bytes, const Dims& dm, int nrows, hipStream_t st);
 
 // lpass.hip : bf16 MFMA temporal kernels (d == 64 or 128, T <= 128)
 bool lpass_supported(const Dims& dm);

@@ -557,8 +557,9 @@ hipError_t launch_flash(const FlashParams& P, hipStream_t st) {
   return hipGetLastError();
 }
 
-int first_frame_splits(const Dims& dm) {
-  const int nqb = (dm.b + BQ - 1) / BQ;
+// Key ranges for exact attention of `nrows` query rows per head over all N keys
+int first_frame_splits(const Dims& dm, int nrows) {
+  const int nqb = (nrows + BQ - 1) / BQ;
   const long long tiles = (dm.N + BK - 1) / BK;
   long long want = (4LL * 256 + (long long)dm.BH * nqb - 1) / ((long long)dm.BH * nqb);  // ~4 workgroups per CU
   long long max_by_len = tiles / 8 > 0 ? tiles / 8 : 1;                                  // >= 8 tiles per split
@@ -607,24 +608,26 @@ hipError_t launch_r_update_flash(const bf16_t* aR, const float* cR, const bf16_t
   return dm.d == 128 ? run(std::integral_constant<int, 128>{}) : run(std::integral_constant<int, 64>{});
 }
 
-size_t first_frame_flash_scratch_bytes(const Dims& dm) {
-  const int ns = first_frame_splits(dm);
+size_t first_frame_flash_scratch_bytes(const Dims& dm, int nrows) {
+  const int ns = first_frame_splits(dm, nrows);
   if (ns == 1) return 0;
-  size_t rows = (size_t)ns * dm.BH * dm.b;
+  size_t rows = (size_t)ns * dm.BH * nrows;
   return rows * dm.d * sizeof(float) + ((rows * sizeof(float) + 255) & ~(size_t)255);
 }
 
+// q, out and lse point at the first row to recompute of head 0 (rows of later heads sit N rows
+// further on, like everything else); k and v at the heads' first tokens.
 hipError_t launch_first_frame_flash(const bf16_t* q, const bf16_t* k, const bf16_t* v, bf16_t* out, float* lse,
-                                    void* scratch, size_t scratch_bytes, const Dims& dm, hipStream_t st) {
+                                    void* scratch, size_t scratch_bytes, const Dims& dm, int nrows, hipStream_t st) {
   FlashParams P = {};
-  const int ns = first_frame_splits(dm);
+  const int ns = first_frame_splits(dm, nrows);
   P.q = q; P.cR = nullptr; P.k = k; P.v = v; P.outk = nullptr; P.outv = out; P.cl = nullptr;
   P.lse = lse;  // written by the kernel itself when one key range covers everything, else by the merge
   P.q_rows_per_problem = dm.N; P.k_rows_per_problem = dm.N;
-  P.nq = dm.b;
+  P.nq = nrows;
   if (dm.N > 0x7fffffffLL - BK) return hipErrorInvalidValue;
   P.nk = (int)dm.N;
-  P.nqb = (dm.b + BQ - 1) / BQ;
+  P.nqb = (nrows + BQ - 1) / BQ;
   P.nsplit = ns;
   const long long tiles = (dm.N + BK - 1) / BK;
   P.keys_per_split = (int)(((tiles + ns - 1) / ns) * BK);
@@ -636,15 +639,15 @@ hipError_t launch_first_frame_flash(const bf16_t* q, const bf16_t* k, const bf16
   P.cr_min = 0.f;
   const bool d128 = dm.d == 128;
   if (ns == 1) return d128 ? launch_flash<128, false, true, 0, false>(P, st) : launch_flash<64, false, true, 0, false>(P, st);
-  const size_t rows = (size_t)ns * dm.BH * dm.b;
+  const size_t rows = (size_t)ns * dm.BH * nrows;
   const size_t need = rows * dm.d * sizeof(float) + ((rows * sizeof(float) + 255) & ~(size_t)255);
   if (scratch == nullptr || scratch_bytes < need) return hipErrorInvalidValue;
   P.part_lse = (float*)scratch;
   P.part_o = (float*)((char*)scratch + ((rows * sizeof(float) + 255) & ~(size_t)255));
   hipError_t e = d128 ? launch_flash<128, false, true, 0, true>(P, st) : launch_flash<64, false, true, 0, true>(P, st);
   if (e != hipSuccess) return e;
-  hipLaunchKernelGGL(merge_splits_kernel, dim3((unsigned)((long long)dm.BH * dm.b)), dim3(dm.d), 0, st, P.part_o,
-                     P.part_lse, out, lse, ns, (long long)dm.BH * dm.b, dm.b, dm.N);
+  hipLaunchKernelGGL(merge_splits_kernel, dim3((unsigned)((long long)dm.BH * nrows)), dim3(dm.d), 0, st, P.part_o,
+                     P.part_lse, out, lse, ns, (long long)dm.BH * nrows, nrows, dm.N);
   return hipGetLastError();
 }
 

@@ -298,8 +298,8 @@ hipError_t launch_l_update_generic(const E* q, const E* aL, const float* cL, con
 
 template <typename E>
 hipError_t launch_first_frame_generic(const E* q, const E* k, const E* v, E* out, float* lse, const Dims& dm,
-                                      hipStream_t st) {
-  dim3 grid(dm.b, dm.BH);
+                                      int nrows, hipStream_t st) {
+  dim3 grid(nrows, dm.BH);  // q, out, lse point at the first row to recompute of head 0
   hipLaunchKernelGGL((first_frame_generic_kernel<E>), grid, dim3(64), 0, st, q, k, v, out, lse, dm.T, dm.b, dm.d,
                      1.0f / sqrtf((float)dm.d));
   return hipGetLastError();
@@ -325,8 +325,8 @@ template hipError_t launch_l_update_generic<float>(const float*, const float*, c
 template hipError_t launch_l_update_generic<bf16_t>(const bf16_t*, const bf16_t*, const float*, const bf16_t*, bf16_t*,
                                                     float*, bf16_t*, const Dims&, float, hipStream_t);
 template hipError_t launch_first_frame_generic<float>(const float*, const float*, const float*, float*, float*,
-                                                      const Dims&, hipStream_t);
+                                                      const Dims&, int, hipStream_t);
 template hipError_t launch_first_frame_generic<bf16_t>(const bf16_t*, const bf16_t*, const bf16_t*, bf16_t*, float*,
-                                                       const Dims&, hipStream_t);
+                                                       const Dims&, int, hipStream_t);
 
 }  // namespace vm

@@ -250,6 +250,31 @@ def test_first_frame_key_range_splits(env, T, b):
     assert U.rel_l2(g, ref) <= U.BF16_REL_L2 and U.max_abs(g, ref) <= U.BF16_MAX_ABS
 
 
+@pytest.mark.parametrize("T,Hs,Ws,d,dt,begin,count", [(4, 4, 4, 32, "f32", 5, 20), (6, 9, 11, 128, "bf16", 300, 270),
+                                                       (6, 9, 11, 64, "bf16", 593, 1), (3, 5, 5, 96, "bf16", 0, 75),
+                                                       (20, 16, 16, 128, "bf16", 1000, 700)])
+def test_recompute_rows_any_range(env, T, Hs, Ws, d, dt, begin, count):
+    """Exact attention for an arbitrary contiguous token range (ranges that straddle frames, a single row, a
+    whole head, a range long enough for the key ranges to be split); nothing outside the range is touched."""
+    torch, binding, dev = env
+    bf16 = dt == "bf16"
+    b, heads = Hs * Ws, 2
+    data = U.structured_heads(T, Hs, Ws, d, 23, heads, bf16)
+    tq, tk, tv = (U.to_device([h[i] for h in data], torch, dev) for i in range(3))
+    out = torch.full_like(tq, 7.0)
+    binding.recompute_rows(tq, tk, tv, T, Hs, Ws, out, begin, count)
+    got = U.from_device(out)
+    rel_tol, abs_tol = _tol(bf16)
+    for h in range(heads):
+        q64, k64, v64 = (U.to_f64(x) for x in data[h])
+        ref = O.softmax_attention(q64[begin:begin + count], k64, v64, 1.0 / math.sqrt(d))
+        g = got[h][begin:begin + count]
+        assert U.rel_l2(g, ref) <= rel_tol and U.max_abs(g, ref) <= abs_tol
+        assert (got[h][:begin] == 7.0).all() and (got[h][begin + count:] == 7.0).all()
+    with pytest.raises(binding.VMonarchError, match="rows"):
+        binding.recompute_rows(tq, tk, tv, T, Hs, Ws, out, T * b - 3, 4)
+
+
 @pytest.mark.parametrize("T,Hs,Ws,d,dt", [(4, 4, 4, 32, "f32"), (1, 3, 3, 128, "bf16"), (9, 7, 9, 128, "bf16"),
                                            (40, 16, 16, 64, "bf16")])
 def test_first_frame_log_sum_exp_output(env, T, Hs, Ws, d, dt):
