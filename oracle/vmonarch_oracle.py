@@ -26,6 +26,11 @@ Readings taken where the paper is silent or inconsistent:
   * 0*log(0) := 0 in c_L.
   * Recomputation overwrites only the output rows of frame 0; the fit is not
     changed by it.
+  * Manual control: "first frame" is the key-frame index k = 0 of c_R[k, i] and
+    c_L[i, k]; the overwrite happens right after the update that produces the
+    term, in every sweep; the c_L constant is a parameter whose default is
+    -log b (the paper's log M for the entropy of a uniform row, with this
+    file's sign c_L = -H).
 
 Pins (tests/test_oracle_*.py): NumPy reshape/transpose for the permutation;
 row-stochastic R, L, M; O == M V with M formed densely; T=1 and b=1 collapse
@@ -33,6 +38,12 @@ to textbook softmax attention; separable logits give exact softmax attention
 for every iteration count; brute-force entropy against c_L and against the
 online accumulator; objective non-decreasing over half-steps and bounded by
 the sum of row log-sum-exps; sum_k c_R[k,i] = T; V == 1 gives O == 1.
+Variants (sink averaging, manual c_R / c_L): with one sweep c_R control changes
+nothing (rows 2 = 3 = 7, 4 = 5 and 6 = 1 of the paper's control table); c_L
+fixed for all frames is independent of the value; a very negative first-frame
+c_L collapses every output to spatial attention within frame 0; frames whose
+c_R is not overwritten keep their R; sink averaging at T = 1 is textbook
+attention and is linear in V with half the Monarch response outside frame 0.
 Backward (Alg. 2): central finite differences of <dO, O> + <dH, H> through
 entropy_attention in every input, rows of dS summing to zero, one-key blocks.
 No worked numeric example is printed in the paper, so no paper value pins it.
@@ -131,7 +142,8 @@ def l_update(aL, cL, Qb):
 # App. A monarch_attention + Sec. 3.3 recomputation
 # --------------------------------------------------------------------------
 def monarch_attention(Q, K, V, m, b, iters, recompute=False, cr_min=0.1,
-                      positions=None, keep_factors=False):
+                      positions=None, keep_factors=False, sink_average=False,
+                      cr_control=0, cl_control=0, cl_value=None):
     """Spatio-temporal Monarch attention for one (batch, head).
 
     Q, K, V: (N, d) float64, N = m*b, token n = j*b + i.
@@ -148,6 +160,16 @@ def monarch_attention(Q, K, V, m, b, iters, recompute=False, cr_min=0.1,
       R, L   last factors, only when keep_factors
     With recompute, O[0] is replaced by exact attention of the frame-0 queries
     over all N keys (Sec. 3.3); nothing else changes.
+
+    Ablation variants (Sec. 4.4 and App. "Manual Control of Monarch Parameters"):
+      sink_average  O <- (softmax(Q K_F1^T / sqrt(d)) V_F1 + O) / 2, every query
+                    against the first frame's keys and values only.
+      cr_control    after every L-update overwrite c_R with 1: 0 never, 1 for
+                    the first frame (k = 0), 2 for all frames.
+      cl_control    after every R-update overwrite c_L with cl_value: 0 never,
+                    1 for the first frame (k = 0), 2 for all frames.  cl_value
+                    defaults to the c_L of a uniform row of the b x b factor,
+                    sum (1/b) log(1/b) = -log b in this file's sign convention.
     """
     N, d = Q.shape
     assert N == m * b and K.shape == (N, d) and V.shape == (N, d) and iters >= 1
@@ -160,9 +182,21 @@ def monarch_attention(Q, K, V, m, b, iters, recompute=False, cr_min=0.1,
     aR = Qs.copy()
     cR = np.ones((m, len(pos)))
     trace = []
+    if cl_value is None:
+        cl_value = -math.log(b)
     for _ in range(iters):
         aL, cL, R = r_update(aR, cR, Kb, cr_min)
+        if cl_control == 1:
+            cL = cL.copy()
+            cL[:, 0] = cl_value
+        elif cl_control == 2:
+            cL = np.full_like(cL, cl_value)
         aR, cR, L = l_update(aL, cL, Qb)
+        if cr_control == 1:
+            cR = cR.copy()
+            cR[0, :] = 1.0
+        elif cr_control == 2:
+            cR = np.ones_like(cR)
         step = dict(aL=aL, cL=cL, aR=aR, cR=cR)
         if keep_factors:
             step.update(R=R, L=L)
@@ -172,6 +206,10 @@ def monarch_attention(Q, K, V, m, b, iters, recompute=False, cr_min=0.1,
     if recompute:
         O = O.copy()
         O[0] = softmax_attention(Q.reshape(m, b, d)[0, pos, :], K, V, s_)
+    if sink_average:
+        Qrows = Q.reshape(m, b, d)[:, pos, :].reshape(-1, d)
+        sink = softmax_attention(Qrows, K[:b], V[:b], s_).reshape(m, len(pos), d)
+        O = 0.5 * (sink + O)
     out = dict(O=O, aL=aL, cL=cL, aR=aR, cR=cR, y=y, trace=trace, positions=pos)
     if keep_factors:
         out.update(R=R, L=L)
