@@ -49,6 +49,16 @@ extern "C" {
 #define VMONARCH_ENTROPY_ONLINE 0   /* Alg. 1 / App. B: third running statistic h beside (m, l) */
 #define VMONARCH_ENTROPY_IDENTITY 1 /* c_L = (aR . alpha_L) * scale - logsumexp, from the outputs */
 
+/* The `recompute` argument of vmonarch_attention[_f32]. */
+#define VMONARCH_RECOMPUTE_NONE 0
+#define VMONARCH_RECOMPUTE_FIRST_FRAME 1 /* Sec. 3.3 */
+#define VMONARCH_SINK_AVERAGE 2          /* Sec. 4.4 ablation: see vmonarch_sink_average */
+
+/* Manual control of c_R / c_L (App. "Manual Control of Monarch Parameters"). */
+#define VMONARCH_CONTROL_NONE 0
+#define VMONARCH_CONTROL_FIRST_FRAME 1 /* key frame k = 0 only */
+#define VMONARCH_CONTROL_ALL_FRAMES 2
+
 /* Library version: major*10000 + minor*100 + patch. */
 int vmonarch_version(void);
 
@@ -61,13 +71,22 @@ const char* vmonarch_last_error(void);
 int vmonarch_set_cr_min(float cr_min);
 float vmonarch_get_cr_min(void);
 
+/* Ablation of App. "Manual Control of Monarch Parameters", applied inside
+ * vmonarch_attention[_f32] in every sweep: right after the L-update c_R is overwritten with 1,
+ * right after the R-update c_L is overwritten with cl_value, each for no frame, key frame 0, or
+ * all frames (VMONARCH_CONTROL_*).  cl_value = NaN selects -log(Hs*Ws): the paper's log M, the
+ * entropy of a uniform row of the b x b factor, with this library's sign c_L = sum R log R.
+ * Defaults: none, none, NaN.  Process-wide.  The getter's pointers may be NULL. */
+int vmonarch_set_manual_control(int cr_control, int cl_control, float cl_value);
+int vmonarch_get_manual_control(int* cr_control, int* cl_control, float* cl_value);
+
 /* Selects VMONARCH_ENTROPY_* for the bf16 MFMA R-update (default ONLINE).  Process-wide. */
 int vmonarch_set_entropy_mode(int mode);
 int vmonarch_get_entropy_mode(void);
 
 /* Benchmark aid.  While enabled, vmonarch_attention[_f32] records a HIP event on the caller's
  * stream before each of its phases ("r_update", "l_update", "r_update_last", "l_update_last",
- * "first_frame") and one at the end.  vmonarch_get_phase_timing waits for the last call's
+ * "first_frame" or "sink_average") and one at the end.  vmonarch_get_phase_timing waits for the last call's
  * final event and writes, for up to `cap` phases, the elapsed milliseconds to ms_host[i] and
  * the phase name to names_host + 32*i (HOST buffers of cap floats / cap*32 chars).  A phase
  * may span more than one kernel launch.  Not thread-safe; off by default. */
@@ -87,8 +106,9 @@ int vmonarch_shutdown(void);
 
 /*
  * Whole path (Eq. 5: O = MonarchAttention(Q, K, V; m = T, b = Hs*Ws, t = iters), then
- * Sec. 3.3 if recompute != 0).  q, k, v, out: [B][heads][N][d].  1/sqrt(d) multiplies Q
- * everywhere Q enters (fit and recomputation alike).
+ * Sec. 3.3 if recompute == VMONARCH_RECOMPUTE_FIRST_FRAME, or the sink averaging of Sec. 4.4 if
+ * recompute == VMONARCH_SINK_AVERAGE; other values are rejected).  q, k, v, out:
+ * [B][heads][N][d].  1/sqrt(d) multiplies Q everywhere Q enters (fit and recomputation alike).
  */
 int vmonarch_attention(const void* q, const void* k, const void* v, void* out, int B, int heads,
                        int T, int Hs, int Ws, int d, int iters, int recompute, void* stream);
@@ -180,6 +200,17 @@ int vmonarch_recompute_rows(const void* q, const void* k, const void* v, void* o
 int vmonarch_recompute_rows_f32(const void* q, const void* k, const void* v, void* out, int B, int heads,
                                 int T, int Hs, int Ws, int d, long long row_begin, long long row_count,
                                 void* stream);
+
+/*
+ * Attention-sink averaging, the alternative to recomputation that Sec. 4.4 compares against:
+ * out <- (out + softmax(Q K_F1^T / sqrt(d)) V_F1) / 2 in place, for all N tokens of every head,
+ * K_F1 / V_F1 the first frame's Hs*Ws keys and values.  `out` holds MonarchAttention(Q, K, V) on
+ * entry (vmonarch_attention with recompute = VMONARCH_SINK_AVERAGE does both).
+ */
+int vmonarch_sink_average(const void* q, const void* k, const void* v, void* out, int B, int heads, int T,
+                          int Hs, int Ws, int d, void* stream);
+int vmonarch_sink_average_f32(const void* q, const void* k, const void* v, void* out, int B, int heads, int T,
+                              int Hs, int Ws, int d, void* stream);
 
 /*
  * Permutation P_(b,N) of Sec. 3.1 (its footnote: reshape to m x b, transpose, flatten).

@@ -31,6 +31,7 @@ EXPORTS = [
     "vmonarch_r_update_lse", "vmonarch_r_update_lse_f32", "vmonarch_first_frame_attention_lse",
     "vmonarch_first_frame_attention_lse_f32", "vmonarch_mfma_probe", "vmonarch_entropy_attention_bwd",
     "vmonarch_entropy_attention_bwd_f32", "vmonarch_recompute_rows", "vmonarch_recompute_rows_f32",
+    "vmonarch_sink_average", "vmonarch_sink_average_f32", "vmonarch_set_manual_control", "vmonarch_get_manual_control",
 ]
 
 
@@ -76,6 +77,10 @@ def lib() -> ctypes.CDLL:
             getattr(L, name).argtypes = [c_void_p] * 12 + dims + [c_float, c_float, c_void_p]
         for name in ("vmonarch_recompute_rows", "vmonarch_recompute_rows_f32"):
             getattr(L, name).argtypes = [c_void_p] * 4 + dims + [ctypes.c_longlong, ctypes.c_longlong, c_void_p]
+        for name in ("vmonarch_sink_average", "vmonarch_sink_average_f32"):
+            getattr(L, name).argtypes = [c_void_p] * 4 + dims + [c_void_p]
+        L.vmonarch_set_manual_control.argtypes = [c_int, c_int, c_float]
+        L.vmonarch_get_manual_control.argtypes = [c_void_p, c_void_p, c_void_p]
         L.vmonarch_mfma_probe.argtypes = [c_void_p, c_void_p, c_int, c_int, c_void_p, c_void_p]
         L.vmonarch_index_maps.argtypes = [c_int, c_int, c_int, c_void_p, c_void_p]
         L.vmonarch_permute_tokens.argtypes = [c_void_p, c_void_p, c_int, c_int, c_int, c_int, c_int, c_int, c_int,
@@ -120,6 +125,16 @@ def get_cr_min() -> float:
     return float(lib().vmonarch_get_cr_min())
 
 
+def set_manual_control(cr_control: int = 0, cl_control: int = 0, cl_value: float = float("nan")) -> None:
+    _check(lib().vmonarch_set_manual_control(cr_control, cl_control, cl_value))
+
+
+def get_manual_control():
+    a, b, c = ctypes.c_int(), ctypes.c_int(), ctypes.c_float()
+    _check(lib().vmonarch_get_manual_control(ctypes.byref(a), ctypes.byref(b), ctypes.byref(c)))
+    return a.value, b.value, c.value
+
+
 def set_entropy_mode(mode: int) -> None:
     _check(lib().vmonarch_set_entropy_mode(mode))
 
@@ -155,13 +170,14 @@ def shutdown() -> None:
 
 
 def attention(q, k, v, T, Hs, Ws, iters=2, recompute=True, out=None):
-    """q, k, v: [B, heads, N, d] bf16 or f32 CUDA tensors -> out of the same shape."""
+    """q, k, v: [B, heads, N, d] bf16 or f32 CUDA tensors -> out of the same shape.
+    recompute: False / 0 none, True / 1 first-frame recomputation, 2 sink averaging."""
     B, heads, N, d = q.shape
     assert N == T * Hs * Ws and k.shape == q.shape and v.shape == q.shape
     if out is None:
         out = torch.empty_like(q)
     fn = getattr(lib(), "vmonarch_attention" + _suffix(q))
-    _check(fn(_ptr(q), _ptr(k), _ptr(v), _ptr(out), B, heads, T, Hs, Ws, d, iters, int(bool(recompute)), _stream()))
+    _check(fn(_ptr(q), _ptr(k), _ptr(v), _ptr(out), B, heads, T, Hs, Ws, d, iters, int(recompute), _stream()))
     return out
 
 
@@ -219,6 +235,14 @@ def recompute_rows(q, k, v, T, Hs, Ws, out, row_begin, row_count):
     B, heads, N, d = q.shape
     fn = getattr(lib(), "vmonarch_recompute_rows" + _suffix(q))
     _check(fn(_ptr(q), _ptr(k), _ptr(v), _ptr(out), B, heads, T, Hs, Ws, d, row_begin, row_count, _stream()))
+    return out
+
+
+def sink_average(q, k, v, T, Hs, Ws, out):
+    """out <- (out + softmax(q K_F1^T / sqrt(d)) V_F1) / 2 in place."""
+    B, heads, N, d = q.shape
+    fn = getattr(lib(), "vmonarch_sink_average" + _suffix(q))
+    _check(fn(_ptr(q), _ptr(k), _ptr(v), _ptr(out), B, heads, T, Hs, Ws, d, _stream()))
     return out
 
 

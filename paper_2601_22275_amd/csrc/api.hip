@@ -10,6 +10,8 @@
 
 #include <mutex>
 
+#include <cmath>
+
 #include "common.h"
 
 using namespace vm;
@@ -18,6 +20,9 @@ namespace {
 
 thread_local char g_err[512] = "";
 float g_cr_min = 0.1f;
+int g_cr_control = VMONARCH_CONTROL_NONE;
+int g_cl_control = VMONARCH_CONTROL_NONE;
+float g_cl_value = NAN;  // NaN: -log(b), the c_L of a uniform row of R
 int g_entropy_mode = VMONARCH_ENTROPY_ONLINE;
 
 std::mutex g_ws_mutex;
@@ -99,7 +104,7 @@ WsLayout ws_layout(const Dims& dm, int iters, int recompute, int elem_bytes) {
   w.aR = off; if (iters > 1) off += tok;
   w.cR = off; if (iters > 1) off += sc;
   w.ff = off;
-  if (recompute && elem_bytes == 2 && flash_supported(dm)) off += align_up(first_frame_flash_scratch_bytes(dm, dm.b));
+  if (recompute == VMONARCH_RECOMPUTE_FIRST_FRAME && elem_bytes == 2 && flash_supported(dm)) off += align_up(first_frame_flash_scratch_bytes(dm, dm.b));
   w.total = off;
   return w;
 }
@@ -204,10 +209,38 @@ int first_frame_any<bf16_t>(const bf16_t* q, const bf16_t* k, const bf16_t* v, b
 }
 
 template <typename E>
+int sink_average_any(const E* q, const E* k, const E* v, E* out, const Dims& dm, hipStream_t st);
+template <>
+int sink_average_any<float>(const float* q, const float* k, const float* v, float* out, const Dims& dm, hipStream_t st) {
+  hipError_t e = launch_sink_average_generic<float>(q, k, v, out, dm, st);
+  return e == hipSuccess ? VMONARCH_OK : hip_fail(e, "sink_average (f32) launch");
+}
+template <>
+int sink_average_any<bf16_t>(const bf16_t* q, const bf16_t* k, const bf16_t* v, bf16_t* out, const Dims& dm,
+                             hipStream_t st) {
+  hipError_t e = flash_supported(dm) ? launch_sink_average_flash(q, k, v, out, dm, st)
+                                     : launch_sink_average_generic<bf16_t>(q, k, v, out, dm, st);
+  return e == hipSuccess ? VMONARCH_OK : hip_fail(e, "sink_average (bf16) launch");
+}
+
+template <typename E>
+int sink_average_impl(const void* q, const void* k, const void* v, void* out, int B, int heads, int T, int Hs, int Ws,
+                      int d, void* stream) {
+  if (!q || !k || !v || !out) return fail(VMONARCH_ERR_INVALID_ARG, "null tensor pointer");
+  if (out == q || out == k || out == v) return fail(VMONARCH_ERR_INVALID_ARG, "out aliases an input");
+  Dims dm;
+  int rc = make_dims(B, heads, T, Hs, Ws, d, &dm);
+  if (rc) return rc;
+  return sink_average_any<E>((const E*)q, (const E*)k, (const E*)v, (E*)out, dm, (hipStream_t)stream);
+}
+
+template <typename E>
 int attention_impl(const void* q_, const void* k_, const void* v_, void* out_, int B, int heads, int T, int Hs, int Ws,
                    int d, int iters, int recompute, void* stream) {
   if (!q_ || !k_ || !v_ || !out_) return fail(VMONARCH_ERR_INVALID_ARG, "null tensor pointer");
   if (iters < 1) return fail(VMONARCH_ERR_INVALID_ARG, "iters=%d must be >= 1", iters);
+  if (recompute < 0 || recompute > VMONARCH_SINK_AVERAGE)
+    return fail(VMONARCH_ERR_INVALID_ARG, "recompute=%d: 0 none, 1 first-frame recomputation, 2 sink averaging", recompute);
   Dims dm;
   int rc = make_dims(B, heads, T, Hs, Ws, d, &dm);
   if (rc) return rc;
@@ -227,6 +260,8 @@ int attention_impl(const void* q_, const void* k_, const void* v_, void* out_, i
   float* cR = (float*)(ws + w.cR);
   const float s = 1.0f / sqrtf((float)d);
   const float cr_min = g_cr_min;
+  const int cr_control = g_cr_control, cl_control = g_cl_control;
+  const float cl_value = std::isnan(g_cl_value) ? -logf((float)dm.b) : g_cl_value;
   // App. A: aR = Q, cR = 1, then `iters` times (R-update; L-update); y = R V and O = L y
   // ride on the last sweep.  Q carries 1/sqrt(d) through row_scale / q_scale.
   g_n_phases = 0;
@@ -236,12 +271,28 @@ int attention_impl(const void* q_, const void* k_, const void* v_, void* out_, i
     rc = r_update_any<E>(sweep == 0 ? q : aR, sweep == 0 ? nullptr : cR, k, last ? v : nullptr, aL, cL,
                          last ? y : nullptr, nullptr, dm, s, cr_min, st);
     if (rc) return rc;
+    // manual control (App. "Manual Control of Monarch Parameters"): overwrite the term just produced,
+    // for key frame 0 (the head's first b entries) or for all frames
+    if (cl_control != VMONARCH_CONTROL_NONE) {
+      hipError_t e = launch_fill_head_prefix(cL, cl_value, cl_control == VMONARCH_CONTROL_ALL_FRAMES ? dm.N : dm.b,
+                                             dm.N, dm.BH, st);
+      if (e != hipSuccess) return hip_fail(e, "c_L control fill");
+    }
     phase_mark(st, last ? "l_update_last" : "l_update");
     rc = l_update_any<E>(q, aL, cL, last ? y : nullptr, last ? nullptr : aR, last ? nullptr : cR, last ? out : nullptr,
                          dm, s, st);
     if (rc) return rc;
+    if (!last && cr_control != VMONARCH_CONTROL_NONE) {
+      hipError_t e = launch_fill_head_prefix(cR, 1.0f, cr_control == VMONARCH_CONTROL_ALL_FRAMES ? dm.N : dm.b, dm.N,
+                                             dm.BH, st);
+      if (e != hipSuccess) return hip_fail(e, "c_R control fill");
+    }
   }
-  if (recompute) {
+  if (recompute == VMONARCH_SINK_AVERAGE) {
+    phase_mark(st, "sink_average");
+    rc = sink_average_any<E>(q, k, v, out, dm, st);
+    if (rc) return rc;
+  } else if (recompute) {
     phase_mark(st, "first_frame");
     rc = first_frame_any<E>(q, k, v, out, nullptr, ws + w.ff, w.total - w.ff, dm, dm.b, st);
     if (rc) return rc;
@@ -343,6 +394,23 @@ int vmonarch_set_cr_min(float cr_min) {
   return VMONARCH_OK;
 }
 float vmonarch_get_cr_min(void) { return g_cr_min; }
+
+int vmonarch_set_manual_control(int cr_control, int cl_control, float cl_value) {
+  if (cr_control < VMONARCH_CONTROL_NONE || cr_control > VMONARCH_CONTROL_ALL_FRAMES ||
+      cl_control < VMONARCH_CONTROL_NONE || cl_control > VMONARCH_CONTROL_ALL_FRAMES)
+    return fail(VMONARCH_ERR_INVALID_ARG, "control modes are 0 (none), 1 (first frame), 2 (all frames)");
+  if (std::isinf(cl_value)) return fail(VMONARCH_ERR_INVALID_ARG, "cl_value must be finite, or NaN for -log(b)");
+  g_cr_control = cr_control;
+  g_cl_control = cl_control;
+  g_cl_value = cl_value;
+  return VMONARCH_OK;
+}
+int vmonarch_get_manual_control(int* cr_control, int* cl_control, float* cl_value) {
+  if (cr_control) *cr_control = g_cr_control;
+  if (cl_control) *cl_control = g_cl_control;
+  if (cl_value) *cl_value = g_cl_value;
+  return VMONARCH_OK;
+}
 
 int vmonarch_set_phase_timing(int enable) {
   g_timing = enable != 0;
@@ -482,6 +550,15 @@ int vmonarch_recompute_rows_f32(const void* q, const void* k, const void* v, voi
                                 int Ws, int d, long long row_begin, long long row_count, void* stream) {
   if (row_count < 1) return fail(VMONARCH_ERR_INVALID_ARG, "row_count must be positive");
   return first_frame_impl<float>(q, k, v, out, nullptr, B, heads, T, Hs, Ws, d, row_begin, row_count, stream);
+}
+
+int vmonarch_sink_average(const void* q, const void* k, const void* v, void* out, int B, int heads, int T, int Hs,
+                          int Ws, int d, void* stream) {
+  return sink_average_impl<bf16_t>(q, k, v, out, B, heads, T, Hs, Ws, d, stream);
+}
+int vmonarch_sink_average_f32(const void* q, const void* k, const void* v, void* out, int B, int heads, int T, int Hs,
+                              int Ws, int d, void* stream) {
+  return sink_average_impl<float>(q, k, v, out, B, heads, T, Hs, Ws, d, stream);
 }
 
 int vmonarch_index_maps(int T, int Hs, int Ws, int32_t* perm_host, int32_t* inv_host) {

@@ -79,6 +79,12 @@ hipError_t launch_first_frame_generic(const E* q, const E* k, const E* v, E* out
                                       int nrows, hipStream_t st);
 hipError_t launch_permute_tokens(const void* in, void* out, const Dims& dm, int row_bytes, int to_pos_major,
                                  hipStream_t st);
+// out <- (out + softmax(q K_F1^T / sqrt(d)) V_F1) / 2 for every token, K_F1 / V_F1 the head's first b rows
+template <typename E>
+hipError_t launch_sink_average_generic(const E* q, const E* k, const E* v, E* out, const Dims& dm, hipStream_t st);
+// p[h * head_stride + r] = value for r < count, h < nheads
+hipError_t launch_fill_head_prefix(float* p, float value, long long count, long long head_stride, int nheads,
+                                   hipStream_t st);
 
 // backward.hip : Alg. 2 on the plain ALUs (D_scratch: BH * N floats)
 size_t entropy_bwd_scratch_bytes(const Dims& dm);
@@ -107,6 +113,9 @@ hipError_t launch_r_update_flash(const bf16_t* aR, const float* cR, const bf16_t
 size_t first_frame_flash_scratch_bytes(const Dims& dm, int nrows);
 hipError_t launch_first_frame_flash(const bf16_t* q, const bf16_t* k, const bf16_t* v, bf16_t* out, float* lse,
                                     void* scratch, size_t scratch_bytes, const Dims& dm, int nrows, hipStream_t st);
+
+hipError_t launch_sink_average_flash(const bf16_t* q, const bf16_t* k, const bf16_t* v, bf16_t* out, const Dims& dm,
+                                     hipStream_t st);
 
 // lpass.hip : bf16 MFMA temporal kernels (d == 64 or 128, T <= 128)
 bool lpass_supported(const Dims& dm);

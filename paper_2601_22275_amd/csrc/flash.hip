@@ -62,7 +62,12 @@ struct FlashParams {
   int blocks_per_xcd;   // ceil(total_blocks / 8)
   float row_scale;
   float cr_min;
+  int blend;            // outv <- (outv + result) / 2 instead of outv <- result
 };
+
+// element-wise (a + b) / 2 of eight bf16 values, in float, rounded once
+__device__ __forceinline__ uint32_t average_bf16x2(uint32_t a, uint32_t b);
+__device__ __forceinline__ uint4 average_bf16x8(uint4 a, uint4 b);
 
 __device__ __forceinline__ bf16x8 lds_read_b128(const char* p) { return *reinterpret_cast<const bf16x8*>(p); }
 
@@ -515,10 +520,22 @@ __global__ void __launch_bounds__(64 * NW) flash_kernel(FlashParams P) {
       const int lc = pc ^ swz(lr);
       if (row_first + lr < P.nq) {
         uint4 w = *reinterpret_cast<const uint4*>(stage + lr * ROW_BYTES + pc * 16);
-        *reinterpret_cast<uint4*>(dst + (qrow0 + row_first + lr) * D + lc * 8) = w;
+        uint4* gp = reinterpret_cast<uint4*>(dst + (qrow0 + row_first + lr) * D + lc * 8);
+        if (P.blend) w = average_bf16x8(w, *gp);
+        *gp = w;
       }
     }
   }
+}
+
+__device__ __forceinline__ uint32_t average_bf16x2(uint32_t a, uint32_t b) {
+  const float lo = 0.5f * (__uint_as_float(a << 16) + __uint_as_float(b << 16));
+  const float hi = 0.5f * (__uint_as_float(a & 0xffff0000u) + __uint_as_float(b & 0xffff0000u));
+  return pack_bf16(lo, hi);
+}
+__device__ __forceinline__ uint4 average_bf16x8(uint4 a, uint4 b) {
+  return make_uint4(average_bf16x2(a.x, b.x), average_bf16x2(a.y, b.y), average_bf16x2(a.z, b.z),
+                    average_bf16x2(a.w, b.w));
 }
 
 // Merge of the key-range partials of the first-frame recomputation: weights 2^(lse - max).
@@ -649,6 +666,29 @@ hipError_t launch_first_frame_flash(const bf16_t* q, const bf16_t* k, const bf16
   hipLaunchKernelGGL(merge_splits_kernel, dim3((unsigned)((long long)dm.BH * nrows)), dim3(dm.d), 0, st, P.part_o,
                      P.part_lse, out, lse, ns, (long long)dm.BH * nrows, nrows, dm.N);
   return hipGetLastError();
+}
+
+// Attention-sink averaging (Sec. 4.4): all N queries of a head against its first frame's b keys,
+// one key range, the normalised rows averaged into `out` by the epilogue.
+hipError_t launch_sink_average_flash(const bf16_t* q, const bf16_t* k, const bf16_t* v, bf16_t* out, const Dims& dm,
+                                     hipStream_t st) {
+  FlashParams P = {};
+  P.q = q; P.k = k; P.v = v; P.outv = out;
+  P.q_rows_per_problem = dm.N; P.k_rows_per_problem = dm.N;
+  if (dm.N > 0x7fffffffLL - BQ) return hipErrorInvalidValue;
+  P.nq = (int)dm.N;
+  P.nk = dm.b;
+  P.nqb = (int)((dm.N + BQ - 1) / BQ);
+  P.nsplit = 1;
+  P.keys_per_split = ((dm.b + BK - 1) / BK) * BK;
+  long long total = (long long)dm.BH * P.nqb;
+  if (total > 0x3fffffffLL) return hipErrorInvalidValue;
+  P.total_blocks = (int)total;
+  P.blocks_per_xcd = (P.total_blocks + 7) / 8;
+  P.row_scale = 1.0f / sqrtf((float)dm.d);
+  P.cr_min = 0.f;
+  P.blend = 1;
+  return dm.d == 128 ? launch_flash<128, false, true, 0, false>(P, st) : launch_flash<64, false, true, 0, false>(P, st);
 }
 
 }  // namespace vm

@@ -31,8 +31,8 @@ __device__ __forceinline__ EntState ent_merge(EntState a, EntState c) {
 // One wave (64 lanes) per query row.  nk keys starting at kbase (and vbase) with row
 // stride d.  Emits out_k = softmax(z) K (if OUT_K), out_v = softmax(z) V (if OUT_V) and
 // cl = sum p log p (if cl != nullptr) and lse = log sum exp z (if lse != nullptr), with
-// z = scale * (qrow . K[l]).
-template <typename E, bool OUT_K, bool OUT_V>
+// z = scale * (qrow . K[l]).  BLEND: out_v <- (out_v + softmax(z) V) / 2 instead.
+template <typename E, bool OUT_K, bool OUT_V, bool BLEND = false>
 __device__ void attend_row(const E* __restrict__ qrow, float scale, const E* __restrict__ kbase,
                            const E* __restrict__ vbase, long long nk, int d, E* __restrict__ out_k,
                            E* __restrict__ out_v, float* __restrict__ cl, float* __restrict__ lse, float* sq,
@@ -104,7 +104,7 @@ __device__ void attend_row(const E* __restrict__ qrow, float scale, const E* __r
     int c = lane + 64 * u;
     if (c < d) {
       if (OUT_K) store_f<E>(out_k + c, acck[u]);
-      if (OUT_V) store_f<E>(out_v + c, accv[u]);
+      if (OUT_V) store_f<E>(out_v + c, BLEND ? 0.5f * (accv[u] + load_f<E>(out_v + c)) : accv[u]);
     }
   }
 }
@@ -138,6 +138,26 @@ __global__ void __launch_bounds__(64) first_frame_generic_kernel(const E* __rest
   const long long head0 = (long long)bh * N;
   attend_row<E, false, true>(q + (head0 + i) * d, scale, k + head0 * d, v + head0 * d, N, d, nullptr,
                              out + (head0 + i) * d, nullptr, lse ? lse + head0 + i : nullptr, sq, sp);
+}
+
+// Attention-sink averaging (Sec. 4.4, the variant marked with a double dagger): every token
+// attends to the first frame's keys and values; the result is averaged into `out`.
+template <typename E>
+__global__ void __launch_bounds__(64) sink_average_generic_kernel(const E* __restrict__ q, const E* __restrict__ k,
+                                                                  const E* __restrict__ v, E* __restrict__ out,
+                                                                  long long N, int b, int d, float scale) {
+  __shared__ float sq[kMaxD];
+  __shared__ float sp[64];
+  const long long row = (long long)blockIdx.y * N + blockIdx.x;
+  const long long head0 = (long long)blockIdx.y * N;
+  attend_row<E, false, true, true>(q + row * d, scale, k + head0 * d, v + head0 * d, b, d, nullptr, out + row * d,
+                                   nullptr, nullptr, sq, sp);
+}
+
+__global__ void __launch_bounds__(256) fill_head_prefix_kernel(float* __restrict__ p, float value, long long count,
+                                                               long long head_stride) {
+  const long long r = (long long)blockIdx.x * 256 + threadIdx.x;
+  if (r < count) p[(long long)blockIdx.y * head_stride + r] = value;
 }
 
 // One workgroup per (position i, batch*head).  The T x T block L_i lives in LDS.
@@ -305,6 +325,25 @@ hipError_t launch_first_frame_generic(const E* q, const E* k, const E* v, E* out
   return hipGetLastError();
 }
 
+template <typename E>
+hipError_t launch_sink_average_generic(const E* q, const E* k, const E* v, E* out, const Dims& dm, hipStream_t st) {
+  if (dm.N > 0x7fffffffLL) return hipErrorInvalidValue;
+  dim3 grid((unsigned)dm.N, dm.BH);
+  hipLaunchKernelGGL((sink_average_generic_kernel<E>), grid, dim3(64), 0, st, q, k, v, out, dm.N, dm.b, dm.d,
+                     1.0f / sqrtf((float)dm.d));
+  return hipGetLastError();
+}
+
+hipError_t launch_fill_head_prefix(float* p, float value, long long count, long long head_stride, int nheads,
+                                   hipStream_t st) {
+  if (count <= 0 || nheads <= 0) return hipSuccess;
+  const long long blocks = (count + 255) / 256;
+  if (blocks > 0x7fffffffLL || nheads > 65535) return hipErrorInvalidValue;
+  hipLaunchKernelGGL(fill_head_prefix_kernel, dim3((unsigned)blocks, nheads), dim3(256), 0, st, p, value, count,
+                     head_stride);
+  return hipGetLastError();
+}
+
 hipError_t launch_permute_tokens(const void* in, void* out, const Dims& dm, int row_bytes, int to_pos_major,
                                  hipStream_t st) {
   long long total = dm.N * (row_bytes / 4);
@@ -328,5 +367,9 @@ template hipError_t launch_first_frame_generic<float>(const float*, const float*
                                                       const Dims&, int, hipStream_t);
 template hipError_t launch_first_frame_generic<bf16_t>(const bf16_t*, const bf16_t*, const bf16_t*, bf16_t*, float*,
                                                        const Dims&, int, hipStream_t);
+template hipError_t launch_sink_average_generic<float>(const float*, const float*, const float*, float*, const Dims&,
+                                                       hipStream_t);
+template hipError_t launch_sink_average_generic<bf16_t>(const bf16_t*, const bf16_t*, const bf16_t*, bf16_t*,
+                                                        const Dims&, hipStream_t);
 
 }  // namespace vm

@@ -134,3 +134,45 @@ def test_backward_at_headline_shape_sampled_frames(env):
             err = U.rel_l2(g[kf], r)
             print(f"backward frame {kf} {name}: rel {err:.2e}")
             assert err <= 1e-2
+
+
+def test_headline_shape_ablation_variants_sampled_positions(env):
+    """Sink averaging and manual c_R / c_L control at the headline shape (2 heads), sampled positions over all
+    frames, plus arbitrary-row recomputation of a range that straddles two frames."""
+    torch, binding, dev = env
+    wl = synth.WORKLOADS["long-81x28x52"]
+    heads = [3, 8]
+    q, k, v = synth.make_inputs(wl, heads=heads)
+    tq, tk, tv = (torch.from_numpy(x).to(dev).view(torch.bfloat16).view(1, len(heads), wl.N, wl.d) for x in (q, k, v))
+    rng = np.random.default_rng(11)
+    pos = np.sort(rng.choice(wl.b, size=12, replace=False))
+    pos[0], pos[-1] = 0, wl.b - 1
+    wide = [tuple(O.widen_bf16(x[hi]) for x in (q, k, v)) for hi in range(len(heads))]
+
+    def check(tag, out, **kw):
+        got = out.float().cpu().numpy()[0].reshape(len(heads), wl.T, wl.b, wl.d)
+        for hi in range(len(heads)):
+            ref = O.monarch_attention(*wide[hi], wl.T, wl.b, wl.iters, positions=pos, **kw)["O"]
+            g = got[hi][:, pos, :]
+            print(f"{tag} head {heads[hi]}: rel {U.rel_l2(g, ref):.2e} max {U.max_abs(g, ref):.2e}")
+            assert U.rel_l2(g, ref) <= U.BF16_REL_L2 and U.max_abs(g, ref) <= U.BF16_MAX_ABS
+
+    check("sink", binding.attention(tq, tk, tv, wl.T, wl.Hs, wl.Ws, wl.iters, 2), sink_average=True)
+    binding.set_manual_control(1, 1)
+    try:
+        out = binding.attention(tq, tk, tv, wl.T, wl.Hs, wl.Ws, wl.iters, True)
+    finally:
+        binding.set_manual_control()
+    check("control cR1 cL1", out, recompute=True, cr_control=1, cl_control=1)
+    # rows [40*b - 700, 40*b + 900) recomputed exactly; everything else keeps the Monarch result
+    base = binding.attention(tq, tk, tv, wl.T, wl.Hs, wl.Ws, wl.iters, False)
+    mixed = base.clone()
+    begin, count = 40 * wl.b - 700, 1600
+    binding.recompute_rows(tq, tk, tv, wl.T, wl.Hs, wl.Ws, mixed, begin, count)
+    assert torch.equal(mixed[:, :, :begin], base[:, :, :begin]) and torch.equal(mixed[:, :, begin + count:], base[:, :, begin + count:])
+    rows = np.sort(rng.choice(count, size=40, replace=False)) + begin
+    rows[0], rows[-1] = begin, begin + count - 1
+    got = mixed.float().cpu().numpy()[0]
+    for hi in range(len(heads)):
+        ref = O.softmax_attention(wide[hi][0][rows], wide[hi][1], wide[hi][2], 1.0 / math.sqrt(wl.d))
+        assert U.rel_l2(got[hi][rows], ref) <= U.BF16_REL_L2 and U.max_abs(got[hi][rows], ref) <= U.BF16_MAX_ABS
