@@ -71,6 +71,13 @@ const char* vmonarch_last_error(void);
 int vmonarch_set_cr_min(float cr_min);
 float vmonarch_get_cr_min(void);
 
+/* bf16 MFMA R-update with values (the last sweep; vmonarch_r_update[_lse] with v != NULL) and online
+ * entropy: 1 (default) forms alpha_L, c_L and y = R V from one evaluation of the logits and the
+ * softmax, two waves sharing a query tile; 0 runs one pass for alpha_L / c_L and a second for y.
+ * Same results up to rounding order.  Process-wide. */
+int vmonarch_set_fused_apply(int enable);
+int vmonarch_get_fused_apply(void);
+
 /* Ablation of App. "Manual Control of Monarch Parameters", applied inside
  * vmonarch_attention[_f32] in every sweep: right after the L-update c_R is overwritten with 1,
  * right after the R-update c_L is overwritten with cl_value, each for no frame, key frame 0, or

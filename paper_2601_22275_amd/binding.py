@@ -32,6 +32,7 @@ EXPORTS = [
     "vmonarch_first_frame_attention_lse_f32", "vmonarch_mfma_probe", "vmonarch_entropy_attention_bwd",
     "vmonarch_entropy_attention_bwd_f32", "vmonarch_recompute_rows", "vmonarch_recompute_rows_f32",
     "vmonarch_sink_average", "vmonarch_sink_average_f32", "vmonarch_set_manual_control", "vmonarch_get_manual_control",
+    "vmonarch_set_fused_apply", "vmonarch_get_fused_apply",
 ]
 
 
@@ -56,6 +57,7 @@ def lib() -> ctypes.CDLL:
         L.vmonarch_set_cr_min.argtypes = [c_float]
         L.vmonarch_get_cr_min.restype = c_float
         L.vmonarch_set_entropy_mode.argtypes = [c_int]
+        L.vmonarch_set_fused_apply.argtypes = [c_int]
         L.vmonarch_workspace_bytes.restype = c_size_t
         L.vmonarch_workspace_bytes.argtypes = dims + [c_int, c_int, c_int]
         L.vmonarch_set_workspace.argtypes = [c_void_p, c_size_t]
@@ -133,6 +135,14 @@ def get_manual_control():
     a, b, c = ctypes.c_int(), ctypes.c_int(), ctypes.c_float()
     _check(lib().vmonarch_get_manual_control(ctypes.byref(a), ctypes.byref(b), ctypes.byref(c)))
     return a.value, b.value, c.value
+
+
+def set_fused_apply(enable: bool) -> None:
+    _check(lib().vmonarch_set_fused_apply(int(enable)))
+
+
+def get_fused_apply() -> bool:
+    return bool(lib().vmonarch_get_fused_apply())
 
 
 def set_entropy_mode(mode: int) -> None:

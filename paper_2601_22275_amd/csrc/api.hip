@@ -20,6 +20,7 @@ namespace {
 
 thread_local char g_err[512] = "";
 float g_cr_min = 0.1f;
+int g_fused_apply = 1;
 int g_cr_control = VMONARCH_CONTROL_NONE;
 int g_cl_control = VMONARCH_CONTROL_NONE;
 float g_cl_value = NAN;  // NaN: -log(b), the c_L of a uniform row of R
@@ -158,7 +159,7 @@ int r_update_any<bf16_t>(const bf16_t* aR, const float* cR, const bf16_t* k, con
                          bf16_t* y, float* lse, const Dims& dm, float row_scale, float cr_min, hipStream_t st) {
   hipError_t e;
   if (flash_supported(dm))
-    e = launch_r_update_flash(aR, cR, k, v, aL, cL, y, lse, dm, row_scale, cr_min, g_entropy_mode, st);
+    e = launch_r_update_flash(aR, cR, k, v, aL, cL, y, lse, dm, row_scale, cr_min, g_entropy_mode, g_fused_apply != 0, st);
   else
     e = launch_r_update_generic<bf16_t>(aR, cR, k, v, aL, cL, y, lse, dm, row_scale, cr_min, st);
   return e == hipSuccess ? VMONARCH_OK : hip_fail(e, "r_update (bf16) launch");
@@ -394,6 +395,12 @@ int vmonarch_set_cr_min(float cr_min) {
   return VMONARCH_OK;
 }
 float vmonarch_get_cr_min(void) { return g_cr_min; }
+
+int vmonarch_set_fused_apply(int enable) {
+  g_fused_apply = enable != 0;
+  return VMONARCH_OK;
+}
+int vmonarch_get_fused_apply(void) { return g_fused_apply; }
 
 int vmonarch_set_manual_control(int cr_control, int cl_control, float cl_value) {
   if (cr_control < VMONARCH_CONTROL_NONE || cr_control > VMONARCH_CONTROL_ALL_FRAMES ||

@@ -106,9 +106,15 @@ hipError_t launch_mfma_probe(const void* operands, float* out, int blocks, int i
 // flash.hip : bf16 MFMA blocked-softmax kernels (d == 64 or 128)
 bool flash_supported(const Dims& dm);
 // lse (optional, may be null): natural-log sum-exp of every query row's logits
+// fused: when v is given and the entropy is accumulated online, form alpha_L, c_L and y in one pass
+// (flash_kv.hip) instead of two
 hipError_t launch_r_update_flash(const bf16_t* aR, const float* cR, const bf16_t* k, const bf16_t* v, bf16_t* aL,
                                  float* cL, bf16_t* y, float* lse, const Dims& dm, float row_scale, float cr_min,
-                                 int entropy_mode, hipStream_t st);
+                                 int entropy_mode, bool fused, hipStream_t st);
+// flash_kv.hip : alpha_L, c_L, lse (optional) and y of one R-update in a single pass (d == 64 or 128)
+hipError_t launch_r_update_flash_fused(const bf16_t* aR, const float* cR, const bf16_t* k, const bf16_t* v, bf16_t* aL,
+                                       float* cL, bf16_t* y, float* lse, const Dims& dm, float row_scale, float cr_min,
+                                       hipStream_t st);
 // exact attention of nrows query rows per head (starting where q / out / lse point) over all N keys
 size_t first_frame_flash_scratch_bytes(const Dims& dm, int nrows);
 hipError_t launch_first_frame_flash(const bf16_t* q, const bf16_t* k, const bf16_t* v, bf16_t* out, float* lse,

@@ -22,133 +22,15 @@
 #include <type_traits>
 
 #include "common.h"
+#include "flash_device.h"
 
 namespace vm {
 
 namespace {
 
-constexpr int BK = 64;          // key rows per LDS tile
-// 32-query tiles per wave.  The code is written for any QT, but two tiles (half the LDS
-// reads per MFMA) need about 300 registers per wave at d = 128 and a wave has 256 with two
-// waves per SIMD, so 1 is the only value in use.
-constexpr int QT = 1;
-constexpr int NW = 8;             // waves per workgroup
-constexpr int BQ = 32 * QT * NW;  // query rows per workgroup
-constexpr int NSLOT = 4;          // LDS tile slots per tensor
-constexpr float LOG2E = 1.4426950408889634f;
-constexpr float LN2 = 0.6931471805599453f;
-constexpr float RESCALE_TH = 8.0f;  // rescale the accumulators only when a row max grows by 2^8
-constexpr float NEG_BIG = -1.0e30f;
-
-struct FlashParams {
-  const bf16_t* q;      // query rows
-  const float* cR;      // per query row, may be null (= 1)
-  const bf16_t* k;
-  const bf16_t* v;
-  bf16_t* outk;         // softmax(z) K   (alpha_L)
-  bf16_t* outv;         // softmax(z) V   (y, or the first-frame output)
-  float* cl;            // sum p log p    (c_L)
-  float* lse;           // natural-log sum-exp of the row's logits, or null
-  float* part_o;        // split mode: [split][problem][nq][D] normalised partial outputs
-  float* part_lse;      // split mode: [split][problem][nq] log2-sum-exp of the partial
-  long long q_rows_per_problem;  // row distance between problems in q / cR / outputs
-  long long k_rows_per_problem;  // row distance between problems in k / v
-  int nq;               // query rows per problem
-  int nk;               // key rows per problem
-  int nqb;              // query blocks per problem
-  int nsplit;           // key splits per (problem, query block)
-  int keys_per_split;   // multiple of BK
-  int total_blocks;     // nproblems * nqb * nsplit
-  int blocks_per_xcd;   // ceil(total_blocks / 8)
-  float row_scale;
-  float cr_min;
-  int blend;            // outv <- (outv + result) / 2 instead of outv <- result
-};
-
 // element-wise (a + b) / 2 of eight bf16 values, in float, rounded once
 __device__ __forceinline__ uint32_t average_bf16x2(uint32_t a, uint32_t b);
 __device__ __forceinline__ uint4 average_bf16x8(uint4 a, uint4 b);
-
-__device__ __forceinline__ bf16x8 lds_read_b128(const char* p) { return *reinterpret_cast<const bf16x8*>(p); }
-
-__device__ __forceinline__ bf16x4 lds_read_tr(const char* p) {
-  return __builtin_amdgcn_ds_read_tr16_b64_v4bf16(
-      (bf16x4 __attribute__((address_space(3)))*)(reinterpret_cast<const bf16x4*>(p)));
-}
-
-__device__ __forceinline__ uint32_t pack_bf16(float a, float b) {
-  // two round-to-nearest-even conversions; the compiler emits v_cvt_pk_bf16_f32
-  typedef __attribute__((__vector_size__(2 * sizeof(__bf16)))) __bf16 bf16x2;
-  bf16x2 r;
-  r[0] = (__bf16)a;
-  r[1] = (__bf16)b;
-  uint32_t u;
-  __builtin_memcpy(&u, &r, 4);
-  return u;
-}
-
-// acc *= alpha for an MFMA accumulator tile.  This file is compiled with the MFMA results
-// in ordinary vector registers (-mllvm -amdgpu-mfma-vgpr-form=1): with two waves per SIMD
-// a wave owns 256 registers in total, the accumulators need only 64 of them, and keeping
-// everything in one register class lets plain VALU code rescale them and spares the
-// accumulation-register round trips.
-__device__ __forceinline__ void scale_acc(f32x16& acc, float alpha) {
-#pragma unroll
-  for (int r = 0; r < 16; ++r) acc[r] *= alpha;
-}
-
-// Row maximum of one 32-key sub-tile for one 32-query tile.  `s` holds the raw logits
-// (aR . K) of query `lane & 31` for keys {8c + 4g + r}; the partner lane (lane ^ 32) holds the
-// other 16 keys and is reached with v_permlane32_swap (no LDS round trip).  Key rows past
-// the end of the range are copies of the last valid row, so they never change a maximum.
-__device__ __forceinline__ float subtile_max(const f32x16& s) {
-  // v_max3: four independent chains of depth 2, then 2 more ops
-  float m0 = fmaxf(fmaxf(s[0], s[1]), s[2]), m1 = fmaxf(fmaxf(s[3], s[4]), s[5]);
-  float m2 = fmaxf(fmaxf(s[6], s[7]), s[8]), m3 = fmaxf(fmaxf(s[9], s[10]), s[11]);
-  m0 = fmaxf(fmaxf(m0, s[12]), s[13]);
-  m1 = fmaxf(fmaxf(m1, s[14]), s[15]);
-  float mx = fmaxf(fmaxf(m0, m1), fmaxf(m2, m3));
-  const unsigned u = __float_as_uint(mx);
-  auto sw = __builtin_amdgcn_permlane32_swap(u, u, false, false);
-  return fmaxf(__uint_as_float(sw[0]), __uint_as_float(sw[1]));
-}
-
-// Probabilities of the sub-tile relative to the reference max `msc` (log2 units):
-// t = s * sc - msc, p = 2^t.  `pb[0..1]` receive the two bf16 B operands (16 keys each) of
-// the O^T += X^T P^T products.  Running sums (Alg. 1's l and, when ENT == 1, h):
-//   lt = sum of the bf16-ROUNDED p (v_dot2 against ones).  The accumulators are divided by
-//        this one, so that the output is an exact convex combination of the rows with
-//        slightly perturbed weights; dividing by the unrounded sum instead leaves a 2^-9
-//        relative error on rows dominated by one key.  It also serves as l in the
-//        log-sum-exp and in H = log l - h / l (error ~1e-3 in c_L, one VALU op per score saved);
-//   h  = sum p * t with the unrounded p.
-template <int ENT>
-__device__ __forceinline__ void subtile_probs(const f32x16& s, float sc, float msc, float& lt, float& h,
-                                              bf16x8 pb[2]) {
-  typedef __attribute__((__vector_size__(2 * sizeof(__bf16)))) __bf16 bf16x2;
-  bf16x2 ones2;
-  ones2[0] = (__bf16)1.0f;
-  ones2[1] = (__bf16)1.0f;
-  float p[16];
-#pragma unroll
-  for (int r = 0; r < 16; ++r) {
-    float t = __builtin_fmaf(s[r], sc, -msc);
-    p[r] = __builtin_amdgcn_exp2f(t);
-    if (ENT == 1) h = __builtin_fmaf(p[r], t, h);
-  }
-#pragma unroll
-  for (int c = 0; c < 2; ++c) {
-    uint32_t w[4];
-#pragma unroll
-    for (int e = 0; e < 4; ++e) {
-      w[e] = pack_bf16(p[8 * c + 2 * e], p[8 * c + 2 * e + 1]);
-      bf16x2 pr;
-      __builtin_memcpy(&pr, &w[e], 4);
-      lt = __builtin_amdgcn_fdot2_f32_bf16(pr, ones2, lt, false);
-    }
-    __builtin_memcpy(&pb[c], w, 16);
-  }
-}
 
 template <int D, bool OUT_K, bool OUT_V, int ENT, bool SPLIT>
 __global__ void __launch_bounds__(64 * NW) flash_kernel(FlashParams P) {
@@ -594,7 +476,9 @@ bool flash_supported(const Dims& dm) { return dm.d == 128 || dm.d == 64; }
 
 hipError_t launch_r_update_flash(const bf16_t* aR, const float* cR, const bf16_t* k, const bf16_t* v, bf16_t* aL,
                                  float* cL, bf16_t* y, float* lse, const Dims& dm, float row_scale, float cr_min,
-                                 int entropy_mode, hipStream_t st) {
+                                 int entropy_mode, bool fused, hipStream_t st) {
+  if (fused && v != nullptr && entropy_mode == VMONARCH_ENTROPY_ONLINE)
+    return launch_r_update_flash_fused(aR, cR, k, v, aL, cL, y, lse, dm, row_scale, cr_min, st);
   FlashParams P = {};
   P.q = aR; P.cR = cR; P.k = k; P.v = v; P.outk = aL; P.outv = y; P.cl = cL; P.lse = lse;
   P.q_rows_per_problem = dm.b; P.k_rows_per_problem = dm.b;
@@ -609,10 +493,7 @@ hipError_t launch_r_update_flash(const bf16_t* aR, const float* cR, const bf16_t
   P.row_scale = row_scale; P.cr_min = cr_min;
   const bool ident = entropy_mode == VMONARCH_ENTROPY_IDENTITY;
   // alpha_L and c_L from one pass over K; y = R V from a second pass that recomputes the
-  // logits.  The single-pass variant (flash_kernel<true, true, ...>, both accumulator sets)
-  // compiles, but the register allocator then spills and serialises every LDS read with its
-  // MFMA; measured on the 81 x 28 x 52 workload the whole call took 6.9 ms with it against
-  // 6.1 ms with two passes.
+  // logits.  (One wave cannot hold both accumulator sets; flash_kv.hip shares them between two.)
   auto run = [&](auto dc) -> hipError_t {
     constexpr int D = decltype(dc)::value;
     hipError_t e = ident ? launch_flash<D, true, false, 2, false>(P, st) : launch_flash<D, true, false, 1, false>(P, st);

@@ -107,11 +107,22 @@ def test_r_update_matches_oracle(env, T, Hs, Ws, d, dt, with_v, with_cr, mode):
             assert U.rel_l2(gy, ref_y) <= rel_tol and U.max_abs(gy, ref_y) <= abs_tol
 
 
+@pytest.fixture(params=[True, False], ids=["one-pass", "two-pass"])
+def fused(request, env):
+    """Both forms of the R-update with values: alpha_L, c_L and y from one pass (two waves per query tile), or a
+    pass for alpha_L / c_L and a second one for y."""
+    binding = env[1]
+    binding.set_fused_apply(request.param)
+    yield request.param
+    binding.set_fused_apply(True)
+
+
 @pytest.mark.parametrize("d", [64, 128])
-@pytest.mark.parametrize("b", [31, 32, 33, 63, 64, 65, 95, 96, 97, 127, 128, 129, 191, 255, 256, 257, 320, 511, 513])
-def test_r_update_at_every_tile_boundary(env, b, d):
-    """One frame of b tokens around every boundary of the blocked kernel: 32-key sub-tiles, 64-key tiles,
-    32-row waves, 256-row query blocks, the four-tile LDS rotation."""
+@pytest.mark.parametrize("b", [31, 32, 33, 63, 64, 65, 95, 96, 97, 127, 128, 129, 191, 192, 193, 255, 256, 257, 320, 511, 513])
+def test_r_update_at_every_tile_boundary(env, b, d, fused):
+    """One frame of b tokens around every boundary of the blocked kernels: 32-key sub-tiles, 64-key tiles (1 to 9
+    of them: every start-up and wind-down path of the step pipelines), 32-row waves, 128- and 256-row query
+    blocks, the four-tile LDS rotation."""
     torch, binding, dev = env
     rng = np.random.default_rng(9000 + 7 * b + d)
     q = U.random_bits(rng, (b, d), 1.2, True)
@@ -127,6 +138,38 @@ def test_r_update_at_every_tile_boundary(env, b, d):
         g = U.from_device(got)[0]
         assert U.rel_l2(g, ref) <= U.BF16_REL_L2 and U.max_abs(g, ref) <= U.BF16_MAX_ABS, (name, b, d)
     assert U.max_abs(U.from_device(cL)[0], O.neg_entropy_rows(R)) <= 2e-2
+
+
+@pytest.mark.parametrize("d", [64, 128])
+def test_r_update_when_the_reference_max_moves_in_every_tile(env, d, fused):
+    """Keys with ever larger logits in later tiles, one spike key per tile, and queries that respond to the
+    spikes with different strength: the kernels' reference maxima move (by more than 2^8) in almost every tile,
+    in the wave that produces the probabilities and in the one that adopts them, while the mass below the
+    spikes still matters for many rows."""
+    torch, binding, dev = env
+    b = 600                                           # 10 key tiles, ragged; 5 query blocks of 128
+    rng = np.random.default_rng(77 + d)
+    qf = rng.normal(size=(b, d)) * 0.8
+    kf = rng.normal(size=(b, d)) * 0.8
+    qf[:, 0] = np.linspace(0.0, 9.0, b)[rng.permutation(b)]   # response of a query to the spikes
+    kf[:, 0] = 0.0
+    for t, l in enumerate(range(17, b, 61)):                   # one spike every 61 keys, growing
+        kf[l, 0] = 7.0 * (t + 1)
+    vf = rng.normal(size=(b, d))
+    q, k, v = (synth.f32_to_bf16_bits(x.astype(np.float32)) for x in (qf, kf, vf))
+    row_scale, cr_min = 1.0 / math.sqrt(d), 0.1
+    tq, tk, tv = (U.to_device([x], torch, dev) for x in (q, k, v))
+    aL, cL, y, lse = binding.r_update_lse(tq, None, tk, tv, 1, 1, b, row_scale, cr_min)
+    z = (U.to_f64(q) @ U.to_f64(k).T) * row_scale
+    assert (z.max(axis=1) - np.median(z, axis=1)).max() > 40  # far more than the 2^8 threshold, for some rows
+    R = O.softmax_rows(z)
+    for name, got, ref in (("aL", aL, R @ U.to_f64(k)), ("y", y, R @ U.to_f64(v))):
+        g = U.from_device(got)[0]
+        tol = max(U.BF16_MAX_ABS, 2.0 ** -8 * float(np.abs(ref).max()))
+        assert U.rel_l2(g, ref) <= U.BF16_REL_L2 and U.max_abs(g, ref) <= tol, (name, d)
+    assert U.max_abs(U.from_device(cL)[0], O.neg_entropy_rows(R)) <= 2e-2
+    ref_lse = np.log(np.exp(z - z.max(axis=1, keepdims=True)).sum(axis=1)) + z.max(axis=1)
+    np.testing.assert_allclose(U.from_device(lse)[0], ref_lse, rtol=2.0 ** -7, atol=2e-2)
 
 
 @pytest.mark.parametrize("T,Hs,Ws,d,dt", [(4, 4, 4, 32, "f32"), (3, 10, 30, 128, "bf16"), (2, 3, 11, 64, "bf16"),

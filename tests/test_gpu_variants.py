@@ -24,6 +24,13 @@ def _tol(bf16):
     return (U.BF16_REL_L2, U.BF16_MAX_ABS) if bf16 else (1e-4, 1e-4)
 
 
+def _abs_tol(abs_tol, ref, bf16):
+    """The bf16 path rounds y and then O to bf16: two half-ulps at the largest magnitude present (2^-7 relative),
+    which exceeds the flat 2e-2 once values pass 2.56.  The control variants sharpen the temporal factor, so
+    single rounded rows of y reach the output undiluted."""
+    return max(abs_tol, 2.0 ** -7 * float(np.abs(ref).max())) if bf16 else abs_tol
+
+
 SHAPES = [
     # T, Hs, Ws, d, dtype
     (4, 4, 4, 32, "f32"),
@@ -114,7 +121,7 @@ def test_manual_control_matches_oracle(env, T, Hs, Ws, d, dt, iters, cr_control,
         free = O.monarch_attention(q64, k64, v64, T, b, iters, recompute=True)["O"].reshape(T * b, d)
         print(f"control T={T} b={b} d={d} {dt} t={iters} cR{cr_control} cL{cl_control}: rel {U.rel_l2(got[h], ref):.2e} "
               f"max {U.max_abs(got[h], ref):.2e}; variant vs plain {U.rel_l2(ref, free):.2e}")
-        assert U.rel_l2(got[h], ref) <= rel_tol and U.max_abs(got[h], ref) <= abs_tol
+        assert U.rel_l2(got[h], ref) <= rel_tol and U.max_abs(got[h], ref) <= _abs_tol(abs_tol, ref, bf16)
         # the setting is off again: the plain call matches the plain oracle
         assert U.rel_l2(plain[h], free) <= rel_tol
 
