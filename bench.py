@@ -289,19 +289,26 @@ def main() -> int:
     elem = 2 if bf16 else 4
     roofline = None
     hbm_phase = None
-    if "r_update" in phases or "r_update_last" in phases:
-        # dominant kernel: the blocked-softmax pass of the R-update (logits + R K), one launch
-        # per sweep; a fitting sweep is exactly one launch of it.
-        if "r_update" in phases:
-            fl, t_ms, what = 4.0 * BH * T * b * b * d, phases["r_update"], "flash_kernel (R-update, logits + R K), fitting sweep"
-        else:
-            fl, t_ms, what = 6.0 * BH * T * b * b * d, phases["r_update_last"], "R-update of the last sweep (two launches: R K pass and R V pass)"
+    fused = bf16 and d in (64, 128) and args.entropy == "online" and binding.get_fused_apply()
+    if "r_update_last" in phases:
+        # dominant kernel (the longest single launch of a call): the R-update of the last sweep, which forms
+        # the logits, R K (alpha_L), c_L and R V (y) in one launch of flash_kv_kernel: three b x b x d products
+        # per frame.  (With the two-pass form, or another entropy mode, the phase is two launches.)
+        fl, t_ms = 6.0 * BH * T * b * b * d, phases["r_update_last"]
+        what = ("flash_kv_kernel (last R-update: logits, R K, c_L and R V in one launch)" if fused
+                else "R-update of the last sweep (two launches: R K pass and R V pass)")
         ach = fl / (t_ms * 1e-3) / 1e12
         roofline = {"bound": "mfma", "achieved": ach, "peak": BF16_MFMA_PEAK_TFLOPS, "unit": "TFLOP/s",
                     "frac": ach / BF16_MFMA_PEAK_TFLOPS,
-                    "traffic": recorded_traffic() if wl.name == "long-81x28x52" and "r_update" in phases else None,
+                    "traffic": recorded_traffic() if wl.name == "long-81x28x52" and fused else None,
                     "kernel": what,
                     "flops_per_launch": fl, "ms_per_launch": t_ms}
+        if "r_update" in phases:
+            # the fitting sweeps' R-update (logits + R K), one launch of flash_kernel each
+            fl2, t2 = 4.0 * BH * T * b * b * d, phases["r_update"]
+            roofline["fitting_r_update"] = {"kernel": "flash_kernel (logits + R K)", "flops_per_launch": fl2,
+                                            "ms_per_launch": t2, "achieved": fl2 / (t2 * 1e-3) / 1e12,
+                                            "frac": fl2 / (t2 * 1e-3) / 1e12 / BF16_MFMA_PEAK_TFLOPS}
     if "l_update" in phases:
         # fitting L-update: reads q and alpha_L, writes alpha_R (3 token tensors) + c_L, c_R
         by = 3.0 * BH * N * d * elem + 2.0 * BH * N * 4

@@ -456,18 +456,42 @@ hipError_t launch_flash(const FlashParams& P, hipStream_t st) {
   return hipGetLastError();
 }
 
-// Key ranges for exact attention of `nrows` query rows per head over all N keys
+int compute_units() {
+  static int cus = 0;  // one device per process is assumed for this tuning value only
+  if (cus == 0) {
+    int dev = 0, n = 0;
+    if (hipGetDevice(&dev) == hipSuccess &&
+        hipDeviceGetAttribute(&n, hipDeviceAttributeMultiprocessorCount, dev) == hipSuccess && n > 0)
+      cus = n;
+    else
+      cus = 256;
+  }
+  return cus;
+}
+
+// Key ranges for exact attention of `nrows` query rows per head over all N keys.  One workgroup
+// occupies a compute unit, and all work items take the same time, so the launch runs in
+// ceil(items / CUs) rounds: the split count is the one that wastes least of the last round,
+// after a charge of a few tiles' worth of time per item for its start-up and wind-down.
 int first_frame_splits(const Dims& dm, int nrows) {
-  const int nqb = (nrows + BQ - 1) / BQ;
+  const long long nqb = (nrows + BQ - 1) / BQ;
   const long long tiles = (dm.N + BK - 1) / BK;
-  long long want = (4LL * 256 + (long long)dm.BH * nqb - 1) / ((long long)dm.BH * nqb);  // ~4 workgroups per CU
-  long long max_by_len = tiles / 8 > 0 ? tiles / 8 : 1;                                  // >= 8 tiles per split
-  long long s = want < max_by_len ? want : max_by_len;
-  if (s < 1) s = 1;
-  if (s > 64) s = 64;
-  const long long per = (tiles + s - 1) / s;  // tiles per split; drop splits that would be empty
-  s = (tiles + per - 1) / per;
-  return (int)s;
+  const long long cus = compute_units();
+  int best = 1;
+  double best_score = -1.0;
+  for (long long s = 1; s <= 64; ++s) {
+    const long long per = (tiles + s - 1) / s;  // tiles per key range
+    if (s > 1 && per < 8) break;
+    if ((tiles + per - 1) / per != s) continue;  // would leave an empty range: the same as a smaller count
+    const long long items = (long long)dm.BH * nqb * s;
+    const long long rounds = (items + cus - 1) / cus;
+    const double score = (double)items / (double)(rounds * cus) * (double)per / (double)(per + 6);
+    if (score > best_score * 1.005) {  // prefer fewer ranges (less merge traffic) unless clearly better
+      best_score = score;
+      best = (int)s;
+    }
+  }
+  return best;
 }
 
 }  // namespace

@@ -282,7 +282,7 @@ __global__ void __launch_bounds__(512) flash_kv_kernel(FlashParams P) {
     if (s + 3 < ntiles) issue_k(s + 3);  // into the slot of tile s-1
     if (s + 1 < ntiles) issue_v(s + 1);  // likewise
   };
-  auto end_step = [&]() __attribute__((always_inline)) {
+  auto end_step = [&](int s) __attribute__((always_inline)) {
     asm volatile("s_waitcnt vmcnt(0)" ::: "memory");
     __syncthreads();  // P(s+1) published, tiles s+3 / s+1 landed, everyone done with tile s
   };
@@ -362,7 +362,7 @@ __global__ void __launch_bounds__(512) flash_kv_kernel(FlashParams P) {
       accumulate(x_tile(s), p_slot(s));
       if (s + 2 < ntiles) logits(smem + ((s + 2) & (KV_KSLOT - 1)) * TILE_BYTES);
     }
-    end_step();
+    end_step(s);
   };
   auto light_edge = [&](int s) __attribute__((always_inline)) {
     begin_step(s);
@@ -375,7 +375,7 @@ __global__ void __launch_bounds__(512) flash_kv_kernel(FlashParams P) {
         if (alpha >= 0.f) scale_all(alpha);
       }
     }
-    end_step();
+    end_step(s);
   };
   {
     int s = 0;
@@ -389,17 +389,17 @@ __global__ void __launch_bounds__(512) flash_kv_kernel(FlashParams P) {
         for (; s + 3 < ntiles; s += 2) {
           begin_step(s);
           heavy_work(s);
-          end_step();
+          end_step(s);
           begin_step(s + 1);
           light_work(s + 1, std::false_type{});
-          end_step();
+          end_step(s + 1);
         }
       } else {
         for (; s + 3 < ntiles; s += 2) {
           begin_step(s);
-          end_step();
+          end_step(s);
           begin_step(s + 1);
-          end_step();
+          end_step(s + 1);
         }
       }
       for (; s < ntiles; s += 2) {
