@@ -463,6 +463,8 @@ __global__ void __launch_bounds__(512) flash_kv_kernel(FlashParams P) {
   }
 }
 
+#undef KV_FENCE
+
 template <int D>
 hipError_t launch_kv(const FlashParams& P, hipStream_t st) {
   constexpr int LDS_BYTES = KvLds<D>::BYTES;
