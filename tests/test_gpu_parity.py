@@ -140,6 +140,35 @@ def test_r_update_at_every_tile_boundary(env, b, d, fused):
     assert U.max_abs(U.from_device(cL)[0], O.neg_entropy_rows(R)) <= 2e-2
 
 
+@pytest.mark.parametrize("seed", range(12))
+def test_r_update_random_shapes_both_forms(env, seed, fused):
+    """Seeded random (T, b, d, c_R) problems: both forms of the R-update with values against the oracle."""
+    torch, binding, dev = env
+    rng = np.random.default_rng(4242 + seed)
+    T = int(rng.integers(1, 6))
+    b = int(rng.integers(1, 700))
+    d = int(rng.choice([64, 128]))
+    heads = 2
+    with_cr = bool(rng.integers(0, 2))
+    q = [U.random_bits(rng, (T * b, d), 1.3, True) for _ in range(heads)]
+    k = [U.random_bits(rng, (T * b, d), 1.3, True) for _ in range(heads)]
+    v = [U.random_bits(rng, (T * b, d), 1.0, True) for _ in range(heads)]
+    cR = (0.05 + 2.5 * rng.random((heads, T * b))).astype(np.float32) if with_cr else None
+    row_scale, cr_min = 1.0 / math.sqrt(d), 0.1
+    tq, tk, tv = (U.to_device(x, torch, dev) for x in (q, k, v))
+    tcr = torch.from_numpy(cR).to(dev).view(1, heads, -1) if with_cr else None
+    aL, cL, y = binding.r_update(tq, tcr, tk, tv, T, 1, b, row_scale, cr_min)
+    gaL, gcL, gy = U.from_device(aL), U.from_device(cL), U.from_device(y)
+    for h in range(heads):
+        c = cR[h].reshape(T, b).astype(np.float64) if with_cr else np.ones((T, b))
+        raL, rcL, R = O.r_update(U.to_f64(q[h]).reshape(T, b, d) * row_scale, c, U.to_f64(k[h]).reshape(T, b, d), cr_min)
+        ry = np.matmul(R, U.to_f64(v[h]).reshape(T, b, d))
+        for name, g, ref in (("aL", gaL[h].reshape(T, b, d), raL.transpose(1, 0, 2)), ("y", gy[h].reshape(T, b, d), ry)):
+            tol = max(U.BF16_MAX_ABS, 2.0 ** -8 * float(np.abs(ref).max()))
+            assert U.rel_l2(g, ref) <= U.BF16_REL_L2 and U.max_abs(g, ref) <= tol, (name, T, b, d, with_cr)
+        assert U.max_abs(gcL[h].reshape(T, b), rcL.T) <= 2e-2, (T, b, d, with_cr)
+
+
 @pytest.mark.parametrize("d", [64, 128])
 def test_r_update_when_the_reference_max_moves_in_every_tile(env, d, fused):
     """Keys with ever larger logits in later tiles, one spike key per tile, and queries that respond to the
