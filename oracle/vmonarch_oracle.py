@@ -108,38 +108,77 @@ def neg_entropy_rows(P: np.ndarray) -> np.ndarray:
 
 
 # --------------------------------------------------------------------------
-# App. A: R_update, L_update
+# Sec. 3.1: the two closed-form half-steps, written from Eqs. (R), (alpha_L, c_L),
+# (L), (alpha_R, c_R) with the paper's index letters: j query frame, i query
+# position, k key frame, l key position, v channel.  One block at a time, every
+# block formed explicitly.  Storage here is [k][i] for the spatial side and [i][k]
+# for the temporal side, as the subscripts of the equations read.
 # --------------------------------------------------------------------------
-def r_update(aR, cR, Kb, cr_min=0.0):
-    """Eq. (R) and Eq. (alpha_L, c_L); App. A R_update.
+def r_update(alpha_R, c_R, K, cr_min=0.0):
+    """Spatial half-step.  Eq. (R): R_k[i, l] = softmax_l(sum_v alpha_R[k,i,v] K[k,l,v] / c_R[k,i]);
+    Eq. (alpha_L, c_L): alpha_L[i,k,v] = sum_l R_k[i,l] K[k,l,v], c_L[i,k] = sum_l R_k[i,l] log R_k[i,l].
 
-    aR (m, s, d), cR (m, s), Kb (m, b, d); s query positions (s == b for the
-    full problem, fewer when only some positions are followed).
-    Returns aL (s, m, d), cL (s, m), R (m, s, b).
+    alpha_R (m, s, d), c_R (m, s), K (m, b, d); s query positions (s == b for the full
+    problem, fewer when only some positions are followed).  c_R is bounded below by cr_min
+    where it divides (Sec. 4.1).  Returns alpha_L (s, m, d), c_L (s, m), R (m, s, b).
     """
-    c = np.maximum(cR, cr_min)
-    Z = np.matmul(aR, Kb.transpose(0, 2, 1)) / c[:, :, None]          # (m, s, b)
-    R = softmax_rows(Z)
-    cL = neg_entropy_rows(R).T                                         # (s, m)
-    aL = np.matmul(R, Kb).transpose(1, 0, 2)                           # (s, m, d)
-    return aL, cL, R
+    m, s, d = alpha_R.shape
+    b = K.shape[1]
+    R = np.empty((m, s, b))
+    alpha_L = np.empty((s, m, d))
+    c_L = np.empty((s, m))
+    for k in range(m):                                   # one b x b block per key frame
+        temperature = np.maximum(c_R[k], cr_min)                         # (s,)
+        logits_il = (alpha_R[k] @ K[k].T) / temperature[:, None]      # sum over v -> [i, l]
+        R_k = softmax_rows(logits_il)                                    # over l
+        R[k] = R_k
+        alpha_L[:, k, :] = R_k @ K[k]                                    # sum over l -> [i, v]
+        c_L[:, k] = neg_entropy_rows(R_k)
+    return alpha_L, c_L, R
 
 
-def l_update(aL, cL, Qb):
-    """Eq. (L) and Eq. (alpha_R, c_R); App. A L_update.
+def l_update(alpha_L, c_L, Q):
+    """Temporal half-step.  Eq. (L): L_i[j, k] = softmax over k of (sum_v alpha_L[i,k,v] Q[i,j,v] - c_L[i,k])
+    (a distribution over key frames for every query frame: the reading that keeps M
+    row-stochastic); Eq. (alpha_R, c_R): alpha_R[k,i,v] = sum_j L_i[j,k] Q[i,j,v],
+    c_R[k,i] = sum_j L_i[j,k].
 
-    aL (s, m, d), cL (s, m), Qb (s, m, d).
-    Returns aR (m, s, d), cR (m, s), L (s, m, m) with L[i][j, k].
+    alpha_L (s, m, d), c_L (s, m), Q (s, m, d) position-major (Q[i, j] is the query of
+    frame j at position i, already carrying 1/sqrt(d)).
+    Returns alpha_R (m, s, d), c_R (m, s), L (s, m, m) with L[i][j, k].
     """
-    U = np.matmul(Qb, aL.transpose(0, 2, 1)) - cL[:, None, :]          # (s, j, k)
-    L = softmax_rows(U)
-    cR = L.sum(axis=1).T                                               # (m, s)
-    aR = np.matmul(L.transpose(0, 2, 1), Qb).transpose(1, 0, 2)        # (m, s, d)
-    return aR, cR, L
+    s, m, d = Q.shape
+    L = np.empty((s, m, m))
+    alpha_R = np.empty((m, s, d))
+    c_R = np.empty((m, s))
+    for i in range(s):                                   # one m x m block per position
+        logits_jk = (Q[i] @ alpha_L[i].T) - c_L[i][None, :]              # sum over v -> [j, k]
+        L_i = softmax_rows(logits_jk)                                    # over k
+        L[i] = L_i
+        alpha_R[:, i, :] = L_i.T @ Q[i]                                  # sum over j -> [k, v]
+        c_R[:, i] = L_i.sum(axis=0)                                      # over j
+    return alpha_R, c_R, L
+
+
+def monarch_apply(L, R, V):
+    """O = M V with M[(j,i),(k,l)] = L_i[j,k] R_k[i,l] (Sec. 3.1), without forming M:
+    y[i,k,v] = sum_l R_k[i,l] V[k,l,v], then O[j,i,v] = sum_k L_i[j,k] y[i,k,v].
+
+    L (s, m, m), R (m, s, b), V (m, b, d).  Returns O (m, s, d) and y (s, m, d).
+    """
+    s, m, _ = L.shape
+    d = V.shape[2]
+    y = np.empty((s, m, d))
+    for k in range(m):
+        y[:, k, :] = R[k] @ V[k]                        # sum over l -> [i, v]
+    O = np.empty((m, s, d))
+    for i in range(s):
+        O[:, i, :] = L[i] @ y[i]                        # sum over k -> [j, v]
+    return O, y
 
 
 # --------------------------------------------------------------------------
-# App. A monarch_attention + Sec. 3.3 recomputation
+# Sec. 3.1 alternating maximisation + Sec. 3.3 recomputation
 # --------------------------------------------------------------------------
 def monarch_attention(Q, K, V, m, b, iters, recompute=False, cr_min=0.1,
                       positions=None, keep_factors=False, sink_average=False,
@@ -173,44 +212,42 @@ def monarch_attention(Q, K, V, m, b, iters, recompute=False, cr_min=0.1,
     """
     N, d = Q.shape
     assert N == m * b and K.shape == (N, d) and V.shape == (N, d) and iters >= 1
-    s_ = 1.0 / math.sqrt(d)
+    inv_sqrt_d = 1.0 / math.sqrt(d)
     pos = np.arange(b) if positions is None else np.asarray(positions, dtype=np.int64)
-    Qs = (Q * s_).reshape(m, b, d)[:, pos, :]                          # Q' (m, s, d)
-    Qb = Qs.transpose(1, 0, 2)                                         # (s, m, d)
-    Kb = K.reshape(m, b, d)
-    Vb = V.reshape(m, b, d)
-    aR = Qs.copy()
-    cR = np.ones((m, len(pos)))
-    trace = []
+    s = len(pos)
+    K_kl = K.reshape(m, b, d)                       # K[k, l, v]
+    V_kl = V.reshape(m, b, d)
+    Q_ji = (Q * inv_sqrt_d).reshape(m, b, d)[:, pos, :]   # scaled queries, [j, i, v]
+    Q_ij = np.ascontiguousarray(Q_ji.transpose(1, 0, 2))  # the same rows position-major, [i, j, v]
     if cl_value is None:
         cl_value = -math.log(b)
+    # L = identity to start with: Eq. (alpha_R, c_R) then gives alpha_R[k,i] = Q[i,k], c_R = 1
+    alpha_R = Q_ji.copy()
+    c_R = np.ones((m, s))
+    trace = []
     for _ in range(iters):
-        aL, cL, R = r_update(aR, cR, Kb, cr_min)
+        alpha_L, c_L, R = r_update(alpha_R, c_R, K_kl, cr_min)
         if cl_control == 1:
-            cL = cL.copy()
-            cL[:, 0] = cl_value
+            c_L[:, 0] = cl_value
         elif cl_control == 2:
-            cL = np.full_like(cL, cl_value)
-        aR, cR, L = l_update(aL, cL, Qb)
+            c_L[:, :] = cl_value
+        alpha_R, c_R, L = l_update(alpha_L, c_L, Q_ij)
         if cr_control == 1:
-            cR = cR.copy()
-            cR[0, :] = 1.0
+            c_R[0, :] = 1.0
         elif cr_control == 2:
-            cR = np.ones_like(cR)
-        step = dict(aL=aL, cL=cL, aR=aR, cR=cR)
+            c_R[:, :] = 1.0
+        step = dict(aL=alpha_L, cL=c_L, aR=alpha_R, cR=c_R)
         if keep_factors:
             step.update(R=R, L=L)
         trace.append(step)
-    y = np.matmul(R, Vb).transpose(1, 0, 2)                            # (s, k, d)
-    O = np.matmul(L, y).transpose(1, 0, 2)                             # (j, s, d)
+    O, y = monarch_apply(L, R, V_kl)
     if recompute:
-        O = O.copy()
-        O[0] = softmax_attention(Q.reshape(m, b, d)[0, pos, :], K, V, s_)
+        O[0] = softmax_attention(Q.reshape(m, b, d)[0, pos, :], K, V, inv_sqrt_d)
     if sink_average:
         Qrows = Q.reshape(m, b, d)[:, pos, :].reshape(-1, d)
-        sink = softmax_attention(Qrows, K[:b], V[:b], s_).reshape(m, len(pos), d)
+        sink = softmax_attention(Qrows, K[:b], V[:b], inv_sqrt_d).reshape(m, s, d)
         O = 0.5 * (sink + O)
-    out = dict(O=O, aL=aL, cL=cL, aR=aR, cR=cR, y=y, trace=trace, positions=pos)
+    out = dict(O=O, aL=alpha_L, cL=c_L, aR=alpha_R, cR=c_R, y=y, trace=trace, positions=pos)
     if keep_factors:
         out.update(R=R, L=L)
     return out
