@@ -209,6 +209,21 @@ int vmonarch_recompute_rows_f32(const void* q, const void* k, const void* v, voi
                                 void* stream);
 
 /*
+ * vmonarch_recompute_rows (bf16) for callers that cannot allocate device memory: code under HIP
+ * graph capture, tight serving loops, harnesses that forbid hipMalloc.  Same arguments, same
+ * kernels, same results; the partial results of the key ranges go to a buffer built into the
+ * library (64 MiB per device, held until the process ends) instead of the workspace, and the
+ * call makes no hipMalloc / hipFree and uses neither the arena nor vmonarch_set_workspace.
+ * B*heads*row_count*ranges*(4 d + 4) bytes must fit the buffer (the range count is the one
+ * vmonarch_recompute_rows would choose); otherwise VMONARCH_ERR_WORKSPACE is returned and nothing
+ * is launched.  All calls on one device share the buffer: calls that overlap in time on one
+ * device (different streams or threads) race; calls on one stream do not.  The first call on a
+ * device looks the buffer's address up (hipGetSymbolAddress): make one call before capturing.
+ */
+int vmonarch_recompute_rows_noalloc(const void* q, const void* k, const void* v, void* out, int B, int heads, int T,
+                                    int Hs, int Ws, int d, long long row_begin, long long row_count, void* stream);
+
+/*
  * Attention-sink averaging, the alternative to recomputation that Sec. 4.4 compares against:
  * out <- (out + softmax(Q K_F1^T / sqrt(d)) V_F1) / 2 in place, for all N tokens of every head,
  * K_F1 / V_F1 the first frame's Hs*Ws keys and values.  `out` holds MonarchAttention(Q, K, V) on

@@ -32,7 +32,7 @@ EXPORTS = [
     "vmonarch_first_frame_attention_lse_f32", "vmonarch_mfma_probe", "vmonarch_entropy_attention_bwd",
     "vmonarch_entropy_attention_bwd_f32", "vmonarch_recompute_rows", "vmonarch_recompute_rows_f32",
     "vmonarch_sink_average", "vmonarch_sink_average_f32", "vmonarch_set_manual_control", "vmonarch_get_manual_control",
-    "vmonarch_set_fused_apply", "vmonarch_get_fused_apply",
+    "vmonarch_set_fused_apply", "vmonarch_get_fused_apply", "vmonarch_recompute_rows_noalloc",
 ]
 
 
@@ -77,7 +77,7 @@ def lib() -> ctypes.CDLL:
             getattr(L, name).argtypes = [c_void_p] * 4 + dims + [c_void_p]
         for name in ("vmonarch_entropy_attention_bwd", "vmonarch_entropy_attention_bwd_f32"):
             getattr(L, name).argtypes = [c_void_p] * 12 + dims + [c_float, c_float, c_void_p]
-        for name in ("vmonarch_recompute_rows", "vmonarch_recompute_rows_f32"):
+        for name in ("vmonarch_recompute_rows", "vmonarch_recompute_rows_f32", "vmonarch_recompute_rows_noalloc"):
             getattr(L, name).argtypes = [c_void_p] * 4 + dims + [ctypes.c_longlong, ctypes.c_longlong, c_void_p]
         for name in ("vmonarch_sink_average", "vmonarch_sink_average_f32"):
             getattr(L, name).argtypes = [c_void_p] * 4 + dims + [c_void_p]
@@ -245,6 +245,15 @@ def recompute_rows(q, k, v, T, Hs, Ws, out, row_begin, row_count):
     B, heads, N, d = q.shape
     fn = getattr(lib(), "vmonarch_recompute_rows" + _suffix(q))
     _check(fn(_ptr(q), _ptr(k), _ptr(v), _ptr(out), B, heads, T, Hs, Ws, d, row_begin, row_count, _stream()))
+    return out
+
+
+def recompute_rows_noalloc(q, k, v, T, Hs, Ws, out, row_begin, row_count):
+    """recompute_rows (bf16) through the entry point that allocates no device memory."""
+    B, heads, N, d = q.shape
+    assert q.dtype == torch.bfloat16
+    _check(lib().vmonarch_recompute_rows_noalloc(_ptr(q), _ptr(k), _ptr(v), _ptr(out), B, heads, T, Hs, Ws, d,
+                                                 row_begin, row_count, _stream()))
     return out
 
 

@@ -16,6 +16,13 @@
 
 using namespace vm;
 
+// Device memory of the entry point that allocates nothing (vmonarch_recompute_rows_noalloc): the
+// partial results of its key ranges.  Every device the library runs on holds one copy until the
+// process ends.  Host code never uses this name as an address: it asks the runtime for the
+// device's copy once (noalloc_scratch below) and passes that pointer on.
+constexpr size_t kNoAllocScratchBytes = (size_t)64 << 20;
+static __device__ __align__(256) unsigned char scratch[kNoAllocScratchBytes];
+
 namespace {
 
 thread_local char g_err[512] = "";
@@ -89,6 +96,30 @@ int make_dims(int B, int heads, int T, int Hs, int Ws, int d, Dims* dm) {
 }
 
 size_t align_up(size_t x) { return (x + 255) & ~(size_t)255; }
+
+// Address of the current device's copy of `scratch`, looked up on the first call per device.
+std::mutex g_scratch_mutex;
+void* g_scratch_ptr[64] = {nullptr};
+void* noalloc_scratch(int* err) {
+  *err = VMONARCH_OK;
+  int dev = 0;
+  hipError_t e = hipGetDevice(&dev);
+  if (e != hipSuccess || dev < 0 || dev >= 64) {
+    *err = fail(VMONARCH_ERR_HIP, "hipGetDevice failed");
+    return nullptr;
+  }
+  std::lock_guard<std::mutex> lk(g_scratch_mutex);
+  if (g_scratch_ptr[dev] == nullptr) {
+    void* p = nullptr;
+    e = hipGetSymbolAddress(&p, HIP_SYMBOL(scratch));
+    if (e != hipSuccess || p == nullptr) {
+      *err = hip_fail(e, "hipGetSymbolAddress(scratch)");
+      return nullptr;
+    }
+    g_scratch_ptr[dev] = p;
+  }
+  return g_scratch_ptr[dev];
+}
 
 struct WsLayout {
   size_t aL, aR, y, cL, cR, ff, total;
@@ -557,6 +588,35 @@ int vmonarch_recompute_rows_f32(const void* q, const void* k, const void* v, voi
                                 int Ws, int d, long long row_begin, long long row_count, void* stream) {
   if (row_count < 1) return fail(VMONARCH_ERR_INVALID_ARG, "row_count must be positive");
   return first_frame_impl<float>(q, k, v, out, nullptr, B, heads, T, Hs, Ws, d, row_begin, row_count, stream);
+}
+
+int vmonarch_recompute_rows_noalloc(const void* q, const void* k, const void* v, void* out, int B, int heads, int T,
+                                    int Hs, int Ws, int d, long long row_begin, long long row_count, void* stream) {
+  if (!q || !k || !v || !out) return fail(VMONARCH_ERR_INVALID_ARG, "null tensor pointer");
+  Dims dm;
+  int rc = make_dims(B, heads, T, Hs, Ws, d, &dm);
+  if (rc) return rc;
+  if (row_begin < 0 || row_count < 1 || row_begin + row_count > dm.N)
+    return fail(VMONARCH_ERR_INVALID_ARG, "rows [%lld, %lld) do not lie inside the %lld tokens of a head", row_begin,
+                row_begin + row_count, dm.N);
+  const int nrows = (int)row_count;
+  void* sp = nullptr;
+  size_t sb = 0;
+  if (flash_supported(dm)) {  // the plain-ALU kernel keeps no partial results
+    sb = align_up(first_frame_flash_scratch_bytes(dm, nrows));
+    if (sb > kNoAllocScratchBytes)
+      return fail(VMONARCH_ERR_WORKSPACE,
+                  "the key-range partials of %d rows x %d heads need %zu bytes, the built-in buffer holds %zu: use "
+                  "vmonarch_recompute_rows, or recompute fewer rows per call",
+                  nrows, dm.BH, sb, kNoAllocScratchBytes);
+    if (sb > 0) {
+      sp = noalloc_scratch(&rc);
+      if (!sp) return rc;
+    }
+  }
+  // every partial the merge reads is written by the key-range pass of the same call: nothing to clear
+  return first_frame_any<bf16_t>((const bf16_t*)q + row_begin * d, (const bf16_t*)k, (const bf16_t*)v,
+                                 (bf16_t*)out + row_begin * d, nullptr, sp, sb, dm, nrows, (hipStream_t)stream);
 }
 
 int vmonarch_sink_average(const void* q, const void* k, const void* v, void* out, int B, int heads, int T, int Hs,
