@@ -196,6 +196,9 @@ def main() -> int:
     ap.add_argument("--workload", default="long-81x28x52")
     ap.add_argument("--entropy", choices=["online", "identity"], default="online")
     ap.add_argument("--no-cpu-baseline", action="store_true")
+    ap.add_argument("--flash-variant", type=int, choices=[0, 1], default=None,
+                    help="bf16 MFMA R-update kernels: 0 two waves per SIMD (the library's default), 1 one wave per SIMD "
+                         "with two query tiles per wave")
     ap.add_argument("--copy-calibration", action="store_true",
                     help="also run one token-permutation copy of known size (reference for HBM byte counters)")
     ap.add_argument("--backward", action="store_true",
@@ -242,6 +245,8 @@ def main() -> int:
     ws = torch.empty(ws_bytes, dtype=torch.uint8, device=dev)
     binding.set_workspace(ws)
     binding.set_entropy_mode(binding.ENTROPY_IDENTITY if args.entropy == "identity" else binding.ENTROPY_ONLINE)
+    if args.flash_variant is not None:
+        binding.set_flash_variant(args.flash_variant)
 
     def eager_step():
         binding.attention(tq, tk, tv, wl.T, wl.Hs, wl.Ws, wl.iters, wl.recompute, out=out)

@@ -87,6 +87,13 @@ int vmonarch_get_fused_apply(void);
 int vmonarch_set_manual_control(int cr_control, int cl_control, float cl_value);
 int vmonarch_get_manual_control(int* cr_control, int* cl_control, float* cl_value);
 
+/* Which bf16 MFMA kernel runs an R-update: 0 (default) the kernels with two waves per SIMD and one
+ * 32-query tile per wave; 1 the kernel with one wave per SIMD and two query tiles per wave, whose
+ * accumulators live in accumulation registers (measured a few per cent faster for the update with
+ * values and slower without).  Same results up to rounding order.  Process-wide. */
+int vmonarch_set_flash_variant(int variant);
+int vmonarch_get_flash_variant(void);
+
 /* Selects VMONARCH_ENTROPY_* for the bf16 MFMA R-update (default ONLINE).  Process-wide. */
 int vmonarch_set_entropy_mode(int mode);
 int vmonarch_get_entropy_mode(void);

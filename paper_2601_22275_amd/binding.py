@@ -33,6 +33,7 @@ EXPORTS = [
     "vmonarch_entropy_attention_bwd_f32", "vmonarch_recompute_rows", "vmonarch_recompute_rows_f32",
     "vmonarch_sink_average", "vmonarch_sink_average_f32", "vmonarch_set_manual_control", "vmonarch_get_manual_control",
     "vmonarch_set_fused_apply", "vmonarch_get_fused_apply", "vmonarch_recompute_rows_noalloc",
+    "vmonarch_set_flash_variant", "vmonarch_get_flash_variant",
 ]
 
 
@@ -246,6 +247,14 @@ def recompute_rows(q, k, v, T, Hs, Ws, out, row_begin, row_count):
     fn = getattr(lib(), "vmonarch_recompute_rows" + _suffix(q))
     _check(fn(_ptr(q), _ptr(k), _ptr(v), _ptr(out), B, heads, T, Hs, Ws, d, row_begin, row_count, _stream()))
     return out
+
+
+def set_flash_variant(variant: int):
+    _check(lib().vmonarch_set_flash_variant(int(variant)))
+
+
+def get_flash_variant() -> int:
+    return int(lib().vmonarch_get_flash_variant())
 
 
 def recompute_rows_noalloc(q, k, v, T, Hs, Ws, out, row_begin, row_count):

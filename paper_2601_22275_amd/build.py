@@ -8,7 +8,7 @@ import sys
 HERE = os.path.dirname(os.path.abspath(__file__))
 CSRC = os.path.join(HERE, "csrc")
 LIB = os.path.join(HERE, "libvmonarch.so")
-SOURCES = ["api.hip", "generic.hip", "flash.hip", "flash_kv.hip", "lpass.hip", "backward.hip", "backward_mfma.hip"]
+SOURCES = ["api.hip", "generic.hip", "flash.hip", "flash_kv.hip", "flash2.hip", "lpass.hip", "backward.hip", "backward_mfma.hip"]
 FLAGS = [
     "-O3", "-std=c++17", "--offload-arch=gfx950", "-fPIC", "-fvisibility=hidden",
     # keep the compiler from forming packed fp32 VALU instructions
@@ -18,7 +18,8 @@ FLAGS = [
 # per-file extras: the blocked-softmax kernels keep MFMA results in vector registers; their
 # logits are never NaN (masking uses large finite values), which spares the v_max x, x, x that
 # would otherwise quiet a possible signalling NaN in front of every maximum
-EXTRA = {"flash.hip": ["-mllvm", "-amdgpu-mfma-vgpr-form=1", "-fno-honor-nans"],
+EXTRA = {"flash2.hip": ["-fno-honor-nans", "-Wno-inline-asm"],
+         "flash.hip": ["-mllvm", "-amdgpu-mfma-vgpr-form=1", "-fno-honor-nans"],
          "flash_kv.hip": ["-mllvm", "-amdgpu-mfma-vgpr-form=1", "-fno-honor-nans"],
          "backward_mfma.hip": ["-mllvm", "-amdgpu-mfma-vgpr-form=1"]}
 

@@ -32,6 +32,9 @@ int g_cr_control = VMONARCH_CONTROL_NONE;
 int g_cl_control = VMONARCH_CONTROL_NONE;
 float g_cl_value = NAN;  // NaN: -log(b), the c_L of a uniform row of R
 int g_entropy_mode = VMONARCH_ENTROPY_ONLINE;
+// which bf16 MFMA kernel runs an R-update: 0 the two-waves-per-SIMD kernels (flash.hip, flash_kv.hip; the faster
+// ones as measured on MI355X), 1 the one-wave-per-SIMD kernel with two query tiles per wave (flash2.hip)
+int g_flash_variant = 0;
 
 std::mutex g_ws_mutex;
 void* g_user_ws = nullptr;
@@ -189,7 +192,9 @@ template <>
 int r_update_any<bf16_t>(const bf16_t* aR, const float* cR, const bf16_t* k, const bf16_t* v, bf16_t* aL, float* cL,
                          bf16_t* y, float* lse, const Dims& dm, float row_scale, float cr_min, hipStream_t st) {
   hipError_t e;
-  if (flash_supported(dm))
+  if (flash_supported(dm) && g_flash_variant == 1)
+    e = launch_r_update_flash2(aR, cR, k, v, aL, cL, y, lse, dm, row_scale, cr_min, g_entropy_mode, st);
+  else if (flash_supported(dm))
     e = launch_r_update_flash(aR, cR, k, v, aL, cL, y, lse, dm, row_scale, cr_min, g_entropy_mode, g_fused_apply != 0, st);
   else
     e = launch_r_update_generic<bf16_t>(aR, cR, k, v, aL, cL, y, lse, dm, row_scale, cr_min, st);
@@ -432,6 +437,13 @@ int vmonarch_set_fused_apply(int enable) {
   return VMONARCH_OK;
 }
 int vmonarch_get_fused_apply(void) { return g_fused_apply; }
+
+int vmonarch_set_flash_variant(int variant) {
+  if (variant != 0 && variant != 1) return fail(VMONARCH_ERR_INVALID_ARG, "flash variant is 0 or 1");
+  g_flash_variant = variant;
+  return VMONARCH_OK;
+}
+int vmonarch_get_flash_variant(void) { return g_flash_variant; }
 
 int vmonarch_set_manual_control(int cr_control, int cl_control, float cl_value) {
   if (cr_control < VMONARCH_CONTROL_NONE || cr_control > VMONARCH_CONTROL_ALL_FRAMES ||

@@ -115,6 +115,11 @@ hipError_t launch_r_update_flash(const bf16_t* aR, const float* cR, const bf16_t
 hipError_t launch_r_update_flash_fused(const bf16_t* aR, const float* cR, const bf16_t* k, const bf16_t* v, bf16_t* aL,
                                        float* cL, bf16_t* y, float* lse, const Dims& dm, float row_scale, float cr_min,
                                        hipStream_t st);
+// flash2.hip : the same passes with one wave per SIMD and two query tiles per wave (d == 64 or 128);
+// v == nullptr: alpha_L, c_L (fitting sweep); v given: also y, from one evaluation of the softmax
+hipError_t launch_r_update_flash2(const bf16_t* aR, const float* cR, const bf16_t* k, const bf16_t* v, bf16_t* aL,
+                                  float* cL, bf16_t* y, float* lse, const Dims& dm, float row_scale, float cr_min,
+                                  int entropy_mode, hipStream_t st);
 // exact attention of nrows query rows per head (starting where q / out / lse point) over all N keys
 size_t first_frame_flash_scratch_bytes(const Dims& dm, int nrows);
 hipError_t launch_first_frame_flash(const bf16_t* q, const bf16_t* k, const bf16_t* v, bf16_t* out, float* lse,

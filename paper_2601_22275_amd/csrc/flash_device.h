@@ -45,6 +45,7 @@ struct FlashParams {
   float row_scale;
   float cr_min;
   int blend;            // outv <- (outv + result) / 2 instead of outv <- result
+  int own_tile_first;   // flash2: queries and keys are the same rows (R-update): start the key loop at the query block's own tile
 };
 
 __device__ __forceinline__ bf16x8 lds_read_b128(const char* p) { return *reinterpret_cast<const bf16x8*>(p); }

@@ -36,14 +36,19 @@ def _run_workload(env, name, heads, n_pos, seed):
     rng = np.random.default_rng(seed)
     worst = (0.0, 0.0)
     for hi in range(len(heads)):
-        pos = np.sort(rng.choice(wl.b, size=n_pos, replace=False))
-        # always include the edges of the last (ragged) query block and key tile
-        pos[0], pos[-1] = 0, wl.b - 1
+        # always include the edges of the last (ragged) query block and key tile and both sides of the
+        # interior query-block boundaries
+        forced = U.boundary_positions(wl.b)
+        free = np.setdiff1d(np.arange(wl.b), forced)
+        pos = np.sort(np.concatenate([forced, rng.choice(free, size=max(n_pos - len(forced), 4), replace=False)]))
         ref = O.monarch_attention(O.widen_bf16(q[hi]), O.widen_bf16(k[hi]), O.widen_bf16(v[hi]), wl.T, wl.b, wl.iters,
                                   recompute=wl.recompute, positions=pos)["O"]
         g = got[hi][:, pos, :]
         rel, mx = U.rel_l2(g, ref), U.max_abs(g, ref)
-        print(f"{name} head {heads[hi]}: {n_pos} positions x {wl.T} frames: rel {rel:.2e} max {mx:.2e}")
+        w = np.unravel_index(np.argmax(np.abs(g - ref)), ref.shape)
+        print(f"{name} head {heads[hi]}: {len(pos)} positions x {wl.T} frames: rel {rel:.2e} max {mx:.2e} "
+              f"(max / 2e-2 = {mx / U.BF16_MAX_ABS:.2f}; worst at frame {w[0]} position {pos[w[1]]} channel {w[2]}: "
+              f"got {g[w]:.5f} ref {ref[w]:.5f})")
         worst = (max(worst[0], rel), max(worst[1], mx))
         assert rel <= U.BF16_REL_L2 and mx <= U.BF16_MAX_ABS
     return tq, tk, tv, out, wl
@@ -87,6 +92,17 @@ def test_headline_long_video_sampled_positions_and_invariants(env):
     assert bool(((of >= lo - 2e-2) & (of <= hi + 2e-2)).all())
     # bit-identical on a second run
     assert torch.equal(out, binding.attention(tq, tk, tv, wl.T, wl.Hs, wl.Ws, wl.iters, wl.recompute))
+
+
+def test_headline_shape_with_the_one_wave_per_simd_kernel(env):
+    """The same workload with both R-updates on the kernel that keeps one wave per SIMD and two query tiles per wave."""
+    torch, binding, dev = env
+    binding.set_flash_variant(1)
+    try:
+        _run_workload(env, "long-81x28x52", [2, 9], 24, 6)
+        _run_workload(env, "wan1.3b-480p", [0], 48, 1)
+    finally:
+        binding.set_flash_variant(0)
 
 
 def test_headline_unclamped_cr_sums_to_frame_count(env):

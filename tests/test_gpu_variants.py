@@ -24,11 +24,32 @@ def _tol(bf16):
     return (U.BF16_REL_L2, U.BF16_MAX_ABS) if bf16 else (1e-4, 1e-4)
 
 
-def _abs_tol(abs_tol, ref, bf16):
-    """The bf16 path rounds y and then O to bf16: two half-ulps at the largest magnitude present (2^-7 relative),
-    which exceeds the flat 2e-2 once values pass 2.56.  The control variants sharpen the temporal factor, so
-    single rounded rows of y reach the output undiluted."""
-    return max(abs_tol, 2.0 ** -7 * float(np.abs(ref).max())) if bf16 else abs_tol
+def _within(got, res, abs_tol, bf16, q_scaled=None):
+    """Element-wise bound against an oracle result `res` (kept factors).  In the bf16 path an output element
+    O[j,i] = sum_k L[j,k] y[k] carries three roundings: of every y[k] when it is stored (half an ulp, at most
+    2^-8 |y[k]|), of every weight L[j,k] as a matrix operand (2^-9 relative) and of the result (at most 2^-8 |O|):
+    (2^-8 + 2^-9) sum_k L[j,k] |y[k]| + 2^-8 |O|.  The weights themselves inherit the bf16 storage of alpha_L:
+    the temporal logit u[j,k] = Q[j] . alpha_L[k] moves by about 2^-9 (sum_v (Q[j,v] alpha_L[k,v])^2)^(1/2) (one
+    independent rounding per channel, root sum of squares), a softmax weight by at most twice the largest such
+    shift of its row, and the output by that times sum_k L[j,k] |y[k]|.  The control variants sharpen the
+    temporal factor: rows of y reach the output undiluted and differences of large rows do not average out, so
+    these terms exceed the flat 2e-2 in places.  Frame 0 is recomputed from all keys and stays under the flat
+    tolerance."""
+    T, s_, d = res["O"].shape
+    ref = res["O"].reshape(T * s_, d)
+    if not bf16:
+        return U.max_abs(got, ref) <= abs_tol, U.max_abs(got, ref) / abs_tol
+    spread = np.einsum("ijk,ikv->jiv", res["L"], np.abs(res["y"]))                       # [j, i, v]
+    du = 2.0 ** -9 * np.sqrt(np.einsum("jiv,ikv->ijk", q_scaled ** 2, res["aL"] ** 2))     # [i, j, k]
+    shift = 2.0 * du.max(axis=2).T                                                       # [j, i]
+    bound = (2.0 ** -8 + 2.0 ** -9 + shift[:, :, None]) * spread + 2.0 ** -8 * np.abs(res["O"])
+    bound = np.maximum(abs_tol, bound).reshape(T * s_, d)
+    bound[:s_] = abs_tol     # the recomputed frame
+    ratio = np.abs(got - ref) / bound
+    w = np.unravel_index(np.argmax(ratio), ratio.shape)
+    print(f"  worst element: token {w[0]} (frame {w[0] // s_}) channel {w[1]}: got {got[w]:.5f} ref {ref[w]:.5f} "
+          f"sum L|y| {spread.reshape(T * s_, d)[w]:.4f} logit shift {shift.reshape(-1)[w[0]]:.4f} bound {bound[w]:.4f}")
+    return float(ratio[w]) <= 1.0, float(ratio[w])
 
 
 SHAPES = [
@@ -116,12 +137,14 @@ def test_manual_control_matches_oracle(env, T, Hs, Ws, d, dt, iters, cr_control,
     rel_tol, abs_tol = _tol(bf16)
     for h in range(heads):
         q64, k64, v64 = (U.to_f64(x) for x in data[h])
-        ref = O.monarch_attention(q64, k64, v64, T, b, iters, recompute=True, cr_control=cr_control,
-                                  cl_control=cl_control, cl_value=cl_value)["O"].reshape(T * b, d)
+        res = O.monarch_attention(q64, k64, v64, T, b, iters, recompute=True, cr_control=cr_control,
+                                  cl_control=cl_control, cl_value=cl_value, keep_factors=True)
+        ref = res["O"].reshape(T * b, d)
         free = O.monarch_attention(q64, k64, v64, T, b, iters, recompute=True)["O"].reshape(T * b, d)
+        ok, ratio = _within(got[h], res, abs_tol, bf16, (q64 / math.sqrt(d)).reshape(T, b, d))
         print(f"control T={T} b={b} d={d} {dt} t={iters} cR{cr_control} cL{cl_control}: rel {U.rel_l2(got[h], ref):.2e} "
-              f"max {U.max_abs(got[h], ref):.2e}; variant vs plain {U.rel_l2(ref, free):.2e}")
-        assert U.rel_l2(got[h], ref) <= rel_tol and U.max_abs(got[h], ref) <= _abs_tol(abs_tol, ref, bf16)
+              f"max {U.max_abs(got[h], ref):.2e} worst/bound {ratio:.2f}; variant vs plain {U.rel_l2(ref, free):.2e}")
+        assert U.rel_l2(got[h], ref) <= rel_tol and ok
         # the setting is off again: the plain call matches the plain oracle
         assert U.rel_l2(plain[h], free) <= rel_tol
 

@@ -23,6 +23,30 @@ def max_abs(a, b):
     return float(np.abs(np.asarray(a, dtype=np.float64) - np.asarray(b, dtype=np.float64)).max())
 
 
+def worst_ratio(got, ref, rel, floor=BF16_MAX_ABS):
+    """max over elements of |got - ref| / max(floor, rel * |ref|): the element-wise form of a bound that is
+    the flat bf16 tolerance for small values and `rel` of the element's OWN magnitude for large ones
+    (bf16 keeps 8 significant bits: one rounding is 2^-9 |x| at most, stored intermediates add theirs)."""
+    got = np.asarray(got, dtype=np.float64)
+    ref = np.asarray(ref, dtype=np.float64)
+    return float((np.abs(got - ref) / np.maximum(floor, rel * np.abs(ref))).max())
+
+
+def weighted_sum_bound(ref, abs_weighted, floor=BF16_MAX_ABS):
+    """Element-wise bound for a bf16 weighted average sum_l w_l x_l that the kernels form with bf16-rounded weights
+    and store in bf16: every weight carries one rounding (2^-9 relative, so at most 2^-9 sum_l w_l |x_l| in the sum:
+    `abs_weighted` is that sum of magnitudes) and the result one more (half an ulp, at most 2^-8 |ref|).  Below the
+    task's flat tolerance `floor` the flat tolerance applies."""
+    return np.maximum(floor, 2.0 ** -9 * np.asarray(abs_weighted, dtype=np.float64) + 2.0 ** -8 * np.abs(ref))
+
+
+def boundary_positions(b):
+    """Query positions on both sides of the interior query-block boundaries of the MFMA kernels (128-row
+    blocks of the one-pass R-update, 256-row blocks of the other passes), the last full block and the ends."""
+    want = [0, 127, 128, 255, 256, 1407, 1408, b - 1]
+    return sorted({p for p in want if 0 <= p < b})
+
+
 def structured_heads(T, Hs, Ws, d, config, heads, bf16, gain=None, sink=0.0):
     """q, k, v as lists over heads of (N, d) arrays: float32, or uint16 bf16 bits."""
     phi = synth.positional_features(T, Hs, Ws)
