@@ -1,7 +1,7 @@
 #!/usr/bin/env python3
 """Throughput of spatio-temporal Monarch attention on one MI355X.
 
-    python bench.py [--gpus 1] [--steps K] [--warmup W] [--workload NAME] [--no-cpu-baseline]
+    python bench.py [--gpus 1] [--steps K] [--warmup W] [--workload NAME] [--iters T] [--no-cpu-baseline]
 
 One step = one call of the whole path (every sweep's R-update and L-update, the apply-to-V
 and the first-frame recomputation) on a seeded synthetic workload that is already resident
@@ -92,17 +92,26 @@ def mfma_probe(torch, binding, dev, cus=256, iters=20000):
     return res
 
 
-def recorded_traffic():
-    """HBM bytes per launch of the dominant kernel from the committed rocprofv3 --pmc summary
-    (FETCH_SIZE and WRITE_SIZE runs scaled by a copy of known size), or None."""
+def recorded_traffic(kernel_that_ran):
+    """HBM bytes per launch of the dominant kernel from the committed rocprofv3 --pmc summary (FETCH_SIZE and
+    WRITE_SIZE runs scaled by a copy of known size), or None.  The summary names the kernel it was taken from:
+    when another kernel ran (a different variant, a renamed or replaced kernel) the figure would be stale and is
+    withheld."""
     path = os.path.join(ROOT, "profiles", "attention_long-81x28x52_hbm_traffic.txt")
+    kernel, value = None, None
     try:
         for line in open(path):
+            if line.startswith("dominant_kernel:"):
+                kernel = line.split(":", 1)[1].strip()
             if line.startswith("dominant_kernel_hbm_bytes_per_launch:"):
-                return float(line.split(":", 1)[1])
+                value = float(line.split(":", 1)[1])
     except OSError:
-        pass
-    return None
+        return None
+    if kernel is None or value is None or not kernel.startswith(kernel_that_ran):
+        print(f"bench.py: profiles/ holds HBM traffic of '{kernel}', the dominant kernel of this run is "
+              f"'{kernel_that_ran}': roofline.traffic withheld", file=sys.stderr)
+        return None
+    return value
 
 
 def sweep_frames(args) -> int:
@@ -194,6 +203,9 @@ def main() -> int:
     ap.add_argument("--steps", type=int, default=20)
     ap.add_argument("--warmup", type=int, default=3)
     ap.add_argument("--workload", default="long-81x28x52")
+    ap.add_argument("--iters", type=int, default=None,
+                    help="number of alternating sweeps (default: the workload's; the 720p workload is also run with 1 and 3 "
+                         "to separate the cost of a sweep)")
     ap.add_argument("--entropy", choices=["online", "identity"], default="online")
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--flash-variant", type=int, choices=[0, 1], default=None,
@@ -226,6 +238,12 @@ def main() -> int:
         return bench_backward(args)
     binding.lib()  # fail loudly when the HIP library is missing
     wl = synth.WORKLOADS[args.workload]
+    if args.iters is not None:
+        if args.iters < 1:
+            print("bench.py: --iters must be at least 1", file=sys.stderr)
+            return 2
+        import dataclasses
+        wl = dataclasses.replace(wl, iters=args.iters)
     dev = torch.device("cuda:0")
     bf16 = wl.dtype == "bf16"
 
@@ -294,33 +312,66 @@ def main() -> int:
     elem = 2 if bf16 else 4
     roofline = None
     hbm_phase = None
-    fused = bf16 and d in (64, 128) and args.entropy == "online" and binding.get_fused_apply()
+    variant = binding.get_flash_variant()
+    fused = bf16 and d in (64, 128) and args.entropy == "online" and binding.get_fused_apply() and variant == 0
     if "r_update_last" in phases:
         # dominant kernel (the longest single launch of a call): the R-update of the last sweep, which forms
-        # the logits, R K (alpha_L), c_L and R V (y) in one launch of flash_kv_kernel: three b x b x d products
-        # per frame.  (With the two-pass form, or another entropy mode, the phase is two launches.)
+        # the logits, R K (alpha_L), c_L and R V (y) in one launch: three b x b x d products per frame.
+        # (With the two-pass form the phase is two launches.)
         fl, t_ms = 6.0 * BH * T * b * b * d, phases["r_update_last"]
-        what = ("flash_kv_kernel (last R-update: logits, R K, c_L and R V in one launch)" if fused
-                else "R-update of the last sweep (two launches: R K pass and R V pass)")
+        if bf16 and d in (64, 128) and variant == 1:
+            kern, what = "flash2_kernel", "flash2_kernel (last R-update: logits, R K, c_L and R V in one launch, one wave per SIMD)"
+        elif fused:
+            kern, what = "flash_kv_kernel", "flash_kv_kernel (last R-update: logits, R K, c_L and R V in one launch)"
+        else:
+            kern, what = "flash_kernel", "R-update of the last sweep (two launches: R K pass and R V pass)"
         ach = fl / (t_ms * 1e-3) / 1e12
         roofline = {"bound": "mfma", "achieved": ach, "peak": BF16_MFMA_PEAK_TFLOPS, "unit": "TFLOP/s",
                     "frac": ach / BF16_MFMA_PEAK_TFLOPS,
-                    "traffic": recorded_traffic() if wl.name == "long-81x28x52" and fused else None,
+                    "traffic": recorded_traffic(kern) if wl.name == "long-81x28x52" and wl.iters == 2 and d == 128 else None,
                     "kernel": what,
                     "flops_per_launch": fl, "ms_per_launch": t_ms}
         if "r_update" in phases:
-            # the fitting sweeps' R-update (logits + R K), one launch of flash_kernel each
+            # the fitting sweeps' R-update (logits + R K), one launch each
             fl2, t2 = 4.0 * BH * T * b * b * d, phases["r_update"]
-            roofline["fitting_r_update"] = {"kernel": "flash_kernel (logits + R K)", "flops_per_launch": fl2,
+            roofline["fitting_r_update"] = {"kernel": "flash2_kernel (logits + R K)" if variant == 1 else "flash_kernel (logits + R K)",
+                                            "flops_per_launch": fl2,
                                             "ms_per_launch": t2, "achieved": fl2 / (t2 * 1e-3) / 1e12,
                                             "frac": fl2 / (t2 * 1e-3) / 1e12 / BF16_MFMA_PEAK_TFLOPS}
+        if "first_frame" in phases:
+            fl3, t3 = 4.0 * BH * b * N * d, phases["first_frame"]
+            roofline["first_frame"] = {"kernel": "flash_kernel over key ranges + merge (exact attention of frame 0)",
+                                       "flops_per_launch": fl3, "ms_per_launch": t3,
+                                       "achieved": fl3 / (t3 * 1e-3) / 1e12,
+                                       "frac": fl3 / (t3 * 1e-3) / 1e12 / BF16_MFMA_PEAK_TFLOPS}
+
+    def hbm(kernel, by, t_ms):
+        return {"kernel": kernel, "bytes_per_launch": by, "ms_per_launch": t_ms, "achieved": by / (t_ms * 1e-3) / 1e9,
+                "peak": HBM_PEAK_GBS, "unit": "GB/s", "frac": by / (t_ms * 1e-3) / 1e9 / HBM_PEAK_GBS}
+
+    hbm_phase = {}
     if "l_update" in phases:
-        # fitting L-update: reads q and alpha_L, writes alpha_R (3 token tensors) + c_L, c_R
-        by = 3.0 * BH * N * d * elem + 2.0 * BH * N * 4
-        hbm_phase = {"kernel": "l_update_mfma_kernel (fitting sweep)", "bytes_per_launch": by,
-                     "ms_per_launch": phases["l_update"], "achieved": by / (phases["l_update"] * 1e-3) / 1e9,
-                     "peak": HBM_PEAK_GBS, "unit": "GB/s",
-                     "frac": by / (phases["l_update"] * 1e-3) / 1e9 / HBM_PEAK_GBS}
+        # fitting L-update: reads q and alpha_L, writes alpha_R (3 token tensors); reads c_L, writes c_R
+        hbm_phase["l_update"] = hbm("L-update of a fitting sweep (q, alpha_L, c_L -> alpha_R, c_R)",
+                                    3.0 * BH * N * d * elem + 2.0 * BH * N * 4, phases["l_update"])
+    if "l_update_last" in phases:
+        # final L-update: reads q, alpha_L, y, writes out (4 token tensors); reads c_L
+        hbm_phase["l_update_last"] = hbm("L-update of the last sweep with the apply-to-V (q, alpha_L, c_L, y -> out)",
+                                         4.0 * BH * N * d * elem + 1.0 * BH * N * 4, phases["l_update_last"])
+    # the stride permutation as a stand-alone copy (never on the fused path): reads and writes every token row once
+    perm_out = torch.empty_like(tq)
+    binding.permute_tokens(tq, wl.T, wl.Hs, wl.Ws, True, out=perm_out)
+    torch.cuda.synchronize()
+    pe = [torch.cuda.Event(enable_timing=True) for _ in range(2)]
+    nperm = max(3, min(args.steps, 10))
+    pe[0].record()
+    for _ in range(nperm):
+        binding.permute_tokens(tq, wl.T, wl.Hs, wl.Ws, True, out=perm_out)
+    pe[1].record()
+    torch.cuda.synchronize()
+    hbm_phase["permute_tokens"] = hbm("vmonarch_permute_tokens, frame-major -> position-major copy of q",
+                                      2.0 * BH * N * d * elem, pe[0].elapsed_time(pe[1]) / nperm)
+    del perm_out
 
     if args.copy_calibration:
         # reads and writes B*heads*N*d*elem bytes each: the yardstick for FETCH_SIZE / WRITE_SIZE
@@ -346,7 +397,7 @@ def main() -> int:
         "algorithmic_tflop_per_call": flops / 1e12,
         "config": {"workload": wl.name, "B": wl.B, "heads": wl.heads, "T": wl.T, "Hs": wl.Hs, "Ws": wl.Ws,
                    "N": wl.N, "d": wl.d, "iters": wl.iters, "recompute": bool(wl.recompute),
-                   "entropy": args.entropy, "launch": "hip graph replay" if args.graph else "eager",
+                   "entropy": args.entropy, "flash_variant": variant, "launch": "hip graph replay" if args.graph else "eager",
                    "input_generation_s": gen_s},
         "phase_ms": phases,
         "roofline": roofline,

@@ -18,14 +18,24 @@
  *   - Entry points without suffix take bfloat16 token tensors; `_f32` twins take float32.
  *     Scalars c_R, c_L are float32 in both.  Accumulation is float32 everywhere.
  *   - `stream` is a hipStream_t passed as void* (NULL = the null stream).  Calls only
- *     enqueue work; they never synchronise the host.
+ *     enqueue work; they never synchronise the host, with one exception: when no workspace
+ *     has been given and the library's own arena has to grow (see vmonarch_set_workspace).
  *   - The library never frees or retains caller memory.  Outputs must not alias inputs.
  *   - Return value: 0 on success, a negative VMONARCH_ERR_* otherwise; nothing is
  *     launched when validation fails.  vmonarch_last_error() describes the last failure
  *     of the calling thread.  No exception crosses this boundary.
- *   - d <= 256 for every entry point.  bf16 with d == 128 or d == 64 runs on the MFMA
- *     kernels (the temporal pass additionally needs T <= 128); other shapes run on slower
- *     plain-ALU kernels with the same results.
+ *   - Concurrency.  vmonarch_attention[_f32], vmonarch_recompute_rows / _tokens,
+ *     vmonarch_first_frame_attention* and vmonarch_entropy_attention_bwd* keep intermediates in
+ *     ONE workspace per process (the buffer of vmonarch_set_workspace, else the library's arena of
+ *     the current device): at most one such call may be in flight per device, on whatever stream,
+ *     unless every concurrent call brings its own buffer (vmonarch_attention_ex with
+ *     options.workspace).  The vmonarch_set_* settings are process-wide and not synchronised: they
+ *     are read when a call is made (a HIP graph captured from a call keeps what was set then);
+ *     vmonarch_attention_ex carries them per call instead.
+ *   - Sizes.  d <= 256, B*heads <= 65535, T <= 65535, N < 2^31 for every entry point.  bf16 with
+ *     d == 128 or d == 64 runs on the MFMA kernels (any T, any Hs*Ws); other shapes and every
+ *     `_f32` entry point run on slower plain-ALU kernels with the same results, whose temporal pass
+ *     keeps a T x T block in LDS and therefore needs T <= 200 (VMONARCH_ERR_UNSUPPORTED beyond).
  *   - (T, Hs, Ws) only enter as m = T blocks of b = Hs*Ws tokens: a general Monarch split
  *     (m, b) of a sequence that is no video is T = m, Hs = 1, Ws = b.
  */
@@ -41,7 +51,7 @@ extern "C" {
 
 #define VMONARCH_OK 0
 #define VMONARCH_ERR_INVALID_ARG (-1) /* null pointer, non-positive size, iters < 1 */
-#define VMONARCH_ERR_UNSUPPORTED (-2) /* d > 256, or a size whose index does not fit */
+#define VMONARCH_ERR_UNSUPPORTED (-2) /* d > 256, a size whose index does not fit, T > 200 on the plain-ALU path */
 #define VMONARCH_ERR_WORKSPACE (-3)   /* caller workspace too small / allocation failed */
 #define VMONARCH_ERR_HIP (-4)         /* a HIP runtime call failed */
 
@@ -98,23 +108,16 @@ int vmonarch_get_flash_variant(void);
 int vmonarch_set_entropy_mode(int mode);
 int vmonarch_get_entropy_mode(void);
 
-/* Benchmark aid.  While enabled, vmonarch_attention[_f32] records a HIP event on the caller's
- * stream before each of its phases ("r_update", "l_update", "r_update_last", "l_update_last",
- * "first_frame" or "sink_average") and one at the end.  vmonarch_get_phase_timing waits for the last call's
- * final event and writes, for up to `cap` phases, the elapsed milliseconds to ms_host[i] and
- * the phase name to names_host + 32*i (HOST buffers of cap floats / cap*32 chars).  A phase
- * may span more than one kernel launch.  Not thread-safe; off by default. */
-int vmonarch_set_phase_timing(int enable);
-int vmonarch_get_phase_timing(int* n_phases, float* ms_host, char* names_host, int cap);
-
 /* Bytes of device scratch vmonarch_attention[_f32] needs for these sizes
  * (elem_bytes = 2 for bf16, 4 for f32).  0 on invalid sizes. */
 size_t vmonarch_workspace_bytes(int B, int heads, int T, int Hs, int Ws, int d, int iters,
                                 int recompute, int elem_bytes);
 
-/* Hands the library a caller-owned device buffer to use as scratch (256-byte aligned).
- * Passing NULL/0 returns to the library-owned arena, which grows on demand with hipMalloc
- * (once per size increase, synchronising) and is released by vmonarch_shutdown(). */
+/* Hands the library a caller-owned device buffer to use as scratch (256-byte aligned) by every later
+ * call of the process.  Passing NULL/0 returns to the library-owned arena (one per device), which
+ * grows on demand: hipDeviceSynchronize + hipFree + hipMalloc, once per size increase, released by
+ * vmonarch_shutdown().  A call that would have to grow the arena while its stream is being captured
+ * into a HIP graph returns VMONARCH_ERR_WORKSPACE instead. */
 int vmonarch_set_workspace(void* dev_ptr, size_t bytes);
 int vmonarch_shutdown(void);
 
@@ -128,6 +131,33 @@ int vmonarch_attention(const void* q, const void* k, const void* v, void* out, i
                        int T, int Hs, int Ws, int d, int iters, int recompute, void* stream);
 int vmonarch_attention_f32(const void* q, const void* k, const void* v, void* out, int B, int heads,
                            int T, int Hs, int Ws, int d, int iters, int recompute, void* stream);
+
+/*
+ * The same call with every setting and the workspace carried by the call instead of the process:
+ * concurrent calls (different streams, different threads) with different settings or different
+ * workspaces do not interfere.  vmonarch_options_init fills in the library's defaults (c_R bound
+ * 0.1 of Sec. 4.1, online entropy of Alg. 1, one-pass last R-update, default kernels, no manual
+ * control, cl_value = NaN for -log(Hs*Ws), no workspace); change fields afterwards.  The process-wide
+ * setters do not affect these calls.  workspace == NULL uses the process-wide workspace / arena.
+ */
+typedef struct vmonarch_options {
+  uint32_t struct_bytes;  /* sizeof(vmonarch_options), set by vmonarch_options_init */
+  float cr_min;           /* see vmonarch_set_cr_min */
+  int entropy_mode;       /* VMONARCH_ENTROPY_* */
+  int fused_apply;        /* see vmonarch_set_fused_apply */
+  int flash_variant;      /* see vmonarch_set_flash_variant */
+  int cr_control;         /* VMONARCH_CONTROL_*, see vmonarch_set_manual_control */
+  int cl_control;
+  float cl_value;
+  void* workspace;        /* device, 256-byte aligned, at least vmonarch_workspace_bytes(...) bytes, or NULL */
+  size_t workspace_bytes;
+} vmonarch_options;
+int vmonarch_options_init(vmonarch_options* options);
+int vmonarch_attention_ex(const void* q, const void* k, const void* v, void* out, int B, int heads, int T, int Hs,
+                          int Ws, int d, int iters, int recompute, const vmonarch_options* options, void* stream);
+int vmonarch_attention_ex_f32(const void* q, const void* k, const void* v, void* out, int B, int heads, int T,
+                              int Hs, int Ws, int d, int iters, int recompute, const vmonarch_options* options,
+                              void* stream);
 
 /*
  * R-update, the intra-frame (spatial) factor (Eq. R with Eq. alpha_L/c_L; App. A R_update;
@@ -271,8 +301,9 @@ int vmonarch_permute_tokens(const void* in, void* out, int B, int heads, int T, 
  * o, lse and H are the forward results (vmonarch_r_update_lse returns lse and cL = -H; its aL is
  * O for V := K, its y is O for V).  dH == NULL means no gradient through the entropy, which is
  * how the paper trains.  No gradient with respect to cR is returned.  Uses the workspace
- * (B*heads*N floats).  Plain-ALU kernels on every shape (no MFMA path yet); results are
- * bit-reproducible: nothing is accumulated across workgroups.
+ * (four floats per query row).  bf16 with d == 64 or 128 runs on MFMA kernels (three passes: dq,
+ * dv, dk), everything else on plain-ALU kernels; results are bit-reproducible: nothing is
+ * accumulated across workgroups.
  */
 int vmonarch_entropy_attention_bwd(const void* q, const float* cR, const void* k, const void* v, const void* o,
                                    const void* dO, const float* lse, const float* H, const float* dH,
@@ -283,19 +314,6 @@ int vmonarch_entropy_attention_bwd_f32(const void* q, const float* cR, const voi
                                        const float* dH, void* dq_out, void* dk_out, void* dv_out, int B,
                                        int heads, int T, int Hs, int Ws, int d, float row_scale, float cr_min,
                                        void* stream);
-
-/*
- * Benchmark aid: the sustained rate of the bf16 matrix instruction the MFMA kernels are built
- * on (v_mfma_f32_32x32x16_bf16) with nothing else running, on operand data the caller
- * supplies.  Launches `blocks` workgroups of 8 waves; every lane reads 8 x 16 bytes from
- * `operands` (device, blocks * 512 * 128 bytes: 4 A and 4 B operands per lane) and issues
- * 8 * iters MFMAs on four accumulators; one float per lane goes to `out` (device,
- * blocks * 512 floats) so that the work is not optimised away.  *flops_host (HOST, may be
- * NULL) receives the floating-point operations of the launch.  The matrix pipe is
- * power-limited: the rate measured with random operands is lower than with zeros.
- */
-int vmonarch_mfma_probe(const void* operands, float* out, int blocks, int iters, double* flops_host,
-                        void* stream);
 
 #ifdef __cplusplus
 }

@@ -34,11 +34,19 @@ EXPORTS = [
     "vmonarch_sink_average", "vmonarch_sink_average_f32", "vmonarch_set_manual_control", "vmonarch_get_manual_control",
     "vmonarch_set_fused_apply", "vmonarch_get_fused_apply", "vmonarch_recompute_rows_noalloc",
     "vmonarch_set_flash_variant", "vmonarch_get_flash_variant",
+    "vmonarch_options_init", "vmonarch_attention_ex", "vmonarch_attention_ex_f32",
 ]
 
 
 class VMonarchError(RuntimeError):
     pass
+
+
+class Options(ctypes.Structure):
+    """vmonarch_options of include/vmonarch.h: the settings and the workspace of one call."""
+    _fields_ = [("struct_bytes", ctypes.c_uint32), ("cr_min", c_float), ("entropy_mode", c_int),
+                ("fused_apply", c_int), ("flash_variant", c_int), ("cr_control", c_int), ("cl_control", c_int),
+                ("cl_value", c_float), ("workspace", c_void_p), ("workspace_bytes", c_size_t)]
 
 
 _lib = None
@@ -78,6 +86,9 @@ def lib() -> ctypes.CDLL:
             getattr(L, name).argtypes = [c_void_p] * 4 + dims + [c_void_p]
         for name in ("vmonarch_entropy_attention_bwd", "vmonarch_entropy_attention_bwd_f32"):
             getattr(L, name).argtypes = [c_void_p] * 12 + dims + [c_float, c_float, c_void_p]
+        L.vmonarch_options_init.argtypes = [ctypes.POINTER(Options)]
+        for name in ("vmonarch_attention_ex", "vmonarch_attention_ex_f32"):
+            getattr(L, name).argtypes = [c_void_p] * 4 + dims + [c_int, c_int, ctypes.POINTER(Options), c_void_p]
         for name in ("vmonarch_recompute_rows", "vmonarch_recompute_rows_f32", "vmonarch_recompute_rows_noalloc"):
             getattr(L, name).argtypes = [c_void_p] * 4 + dims + [ctypes.c_longlong, ctypes.c_longlong, c_void_p]
         for name in ("vmonarch_sink_average", "vmonarch_sink_average_f32"):
@@ -189,6 +200,28 @@ def attention(q, k, v, T, Hs, Ws, iters=2, recompute=True, out=None):
         out = torch.empty_like(q)
     fn = getattr(lib(), "vmonarch_attention" + _suffix(q))
     _check(fn(_ptr(q), _ptr(k), _ptr(v), _ptr(out), B, heads, T, Hs, Ws, d, iters, int(recompute), _stream()))
+    return out
+
+
+def default_options() -> Options:
+    """A vmonarch_options filled with the library's defaults."""
+    o = Options()
+    _check(lib().vmonarch_options_init(ctypes.byref(o)))
+    return o
+
+
+def attention_ex(q, k, v, T, Hs, Ws, iters, recompute, options: Options, out=None, workspace=None):
+    """attention() with the settings (and optionally the workspace tensor) carried by this call."""
+    B, heads, N, d = q.shape
+    assert N == T * Hs * Ws and k.shape == q.shape and v.shape == q.shape
+    if out is None:
+        out = torch.empty_like(q)
+    if workspace is not None:
+        options.workspace = workspace.data_ptr()
+        options.workspace_bytes = workspace.numel() * workspace.element_size()
+    fn = getattr(lib(), "vmonarch_attention_ex" + _suffix(q))
+    _check(fn(_ptr(q), _ptr(k), _ptr(v), _ptr(out), B, heads, T, Hs, Ws, d, iters, int(recompute),
+              ctypes.byref(options), _stream()))
     return out
 
 
@@ -312,9 +345,10 @@ def index_maps(T, Hs, Ws):
     return perm, inv
 
 
-def permute_tokens(x, T, Hs, Ws, to_position_major=True):
+def permute_tokens(x, T, Hs, Ws, to_position_major=True, out=None):
     B, heads, N, d = x.shape
-    out = torch.empty_like(x)
+    if out is None:
+        out = torch.empty_like(x)
     _check(lib().vmonarch_permute_tokens(_ptr(x), _ptr(out), B, heads, T, Hs, Ws, d * x.element_size(),
                                          int(bool(to_position_major)), _stream()))
     return out

@@ -2,6 +2,7 @@
 // the whole path (App. A monarch_attention loop + Sec. 3.3 recomputation).  See
 // include/vmonarch.h for the contract of every entry point.
 #include "../../include/vmonarch.h"
+#include "../../include/vmonarch_bench.h"
 
 #include <math.h>
 #include <stdarg.h>
@@ -144,10 +145,20 @@ WsLayout ws_layout(const Dims& dm, int iters, int recompute, int elem_bytes) {
   return w;
 }
 
-// Returns scratch of at least `bytes` on the current device, or nullptr with g_err set.
-void* get_workspace(size_t bytes, int* err) {
-  std::lock_guard<std::mutex> lk(g_ws_mutex);
+// Returns scratch of at least `bytes` on the current device, or nullptr with g_err set: the call's own buffer
+// if it brought one, else the process-wide caller workspace, else the library's grow-only arena.  Growing the
+// arena synchronises the device and allocates, which a stream that is being captured into a graph forbids:
+// then the call fails instead.
+void* get_workspace(size_t bytes, int* err, void* call_ws = nullptr, size_t call_ws_bytes = 0, hipStream_t st = nullptr) {
   *err = VMONARCH_OK;
+  if (call_ws != nullptr) {
+    if (call_ws_bytes < bytes) {
+      *err = fail(VMONARCH_ERR_WORKSPACE, "the call's workspace has %zu bytes, %zu needed", call_ws_bytes, bytes);
+      return nullptr;
+    }
+    return call_ws;
+  }
+  std::lock_guard<std::mutex> lk(g_ws_mutex);
   if (g_user_ws != nullptr) {
     if (g_user_ws_bytes < bytes) {
       *err = fail(VMONARCH_ERR_WORKSPACE, "caller workspace has %zu bytes, %zu needed", g_user_ws_bytes, bytes);
@@ -162,6 +173,14 @@ void* get_workspace(size_t bytes, int* err) {
     return nullptr;
   }
   if (g_arena_bytes[dev] < bytes) {
+    hipStreamCaptureStatus cap = hipStreamCaptureStatusNone;
+    if (hipStreamIsCapturing(st, &cap) == hipSuccess && cap != hipStreamCaptureStatusNone) {
+      *err = fail(VMONARCH_ERR_WORKSPACE,
+                  "the library's arena would have to grow to %zu bytes while the stream is being captured: give the "
+                  "call a workspace (vmonarch_set_workspace or vmonarch_options) or run it once before capturing",
+                  bytes);
+      return nullptr;
+    }
     if (g_arena[dev] != nullptr) {
       (void)hipDeviceSynchronize();
       (void)hipFree(g_arena[dev]);
@@ -179,23 +198,52 @@ void* get_workspace(size_t bytes, int* err) {
   return g_arena[dev];
 }
 
+// Settings of one call: the process-wide defaults (the setters above write them), or a caller's vmonarch_options.
+struct Settings {
+  float cr_min;
+  int entropy_mode;
+  int fused_apply;
+  int flash_variant;
+  int cr_control;
+  int cl_control;
+  float cl_value;
+  void* workspace;  // null: the process-wide workspace / arena
+  size_t workspace_bytes;
+};
+
+Settings current_settings() {
+  Settings s;
+  s.cr_min = g_cr_min;
+  s.entropy_mode = g_entropy_mode;
+  s.fused_apply = g_fused_apply;
+  s.flash_variant = g_flash_variant;
+  s.cr_control = g_cr_control;
+  s.cl_control = g_cl_control;
+  s.cl_value = g_cl_value;
+  s.workspace = nullptr;
+  s.workspace_bytes = 0;
+  return s;
+}
+
 template <typename E>
 int r_update_any(const E* aR, const float* cR, const E* k, const E* v, E* aL, float* cL, E* y, float* lse,
-                 const Dims& dm, float row_scale, float cr_min, hipStream_t st);
+                 const Dims& dm, float row_scale, float cr_min, const Settings& cfg, hipStream_t st);
 template <>
 int r_update_any<float>(const float* aR, const float* cR, const float* k, const float* v, float* aL, float* cL,
-                        float* y, float* lse, const Dims& dm, float row_scale, float cr_min, hipStream_t st) {
+                        float* y, float* lse, const Dims& dm, float row_scale, float cr_min, const Settings&,
+                        hipStream_t st) {
   hipError_t e = launch_r_update_generic<float>(aR, cR, k, v, aL, cL, y, lse, dm, row_scale, cr_min, st);
   return e == hipSuccess ? VMONARCH_OK : hip_fail(e, "r_update (plain-ALU f32) launch");
 }
 template <>
 int r_update_any<bf16_t>(const bf16_t* aR, const float* cR, const bf16_t* k, const bf16_t* v, bf16_t* aL, float* cL,
-                         bf16_t* y, float* lse, const Dims& dm, float row_scale, float cr_min, hipStream_t st) {
+                         bf16_t* y, float* lse, const Dims& dm, float row_scale, float cr_min, const Settings& cfg,
+                         hipStream_t st) {
   hipError_t e;
-  if (flash_supported(dm) && g_flash_variant == 1)
-    e = launch_r_update_flash2(aR, cR, k, v, aL, cL, y, lse, dm, row_scale, cr_min, g_entropy_mode, st);
+  if (flash_supported(dm) && cfg.flash_variant == 1)
+    e = launch_r_update_flash2(aR, cR, k, v, aL, cL, y, lse, dm, row_scale, cr_min, cfg.entropy_mode, st);
   else if (flash_supported(dm))
-    e = launch_r_update_flash(aR, cR, k, v, aL, cL, y, lse, dm, row_scale, cr_min, g_entropy_mode, g_fused_apply != 0, st);
+    e = launch_r_update_flash(aR, cR, k, v, aL, cL, y, lse, dm, row_scale, cr_min, cfg.entropy_mode, cfg.fused_apply != 0, st);
   else
     e = launch_r_update_generic<bf16_t>(aR, cR, k, v, aL, cL, y, lse, dm, row_scale, cr_min, st);
   return e == hipSuccess ? VMONARCH_OK : hip_fail(e, "r_update (bf16) launch");
@@ -273,7 +321,7 @@ int sink_average_impl(const void* q, const void* k, const void* v, void* out, in
 
 template <typename E>
 int attention_impl(const void* q_, const void* k_, const void* v_, void* out_, int B, int heads, int T, int Hs, int Ws,
-                   int d, int iters, int recompute, void* stream) {
+                   int d, int iters, int recompute, const Settings& cfg, void* stream) {
   if (!q_ || !k_ || !v_ || !out_) return fail(VMONARCH_ERR_INVALID_ARG, "null tensor pointer");
   if (iters < 1) return fail(VMONARCH_ERR_INVALID_ARG, "iters=%d must be >= 1", iters);
   if (recompute < 0 || recompute > VMONARCH_SINK_AVERAGE)
@@ -288,7 +336,8 @@ int attention_impl(const void* q_, const void* k_, const void* v_, void* out_, i
   E* out = (E*)out_;
   hipStream_t st = (hipStream_t)stream;
   WsLayout w = ws_layout(dm, iters, recompute, (int)sizeof(E));
-  char* ws = (char*)get_workspace(w.total, &rc);  // w.total > 0: alpha_L, y and c_L are always needed
+  // w.total > 0: alpha_L, y and c_L are always needed
+  char* ws = (char*)get_workspace(w.total, &rc, cfg.workspace, cfg.workspace_bytes, st);
   if (!ws) return rc;
   E* aL = (E*)(ws + w.aL);
   E* y = (E*)(ws + w.y);
@@ -296,17 +345,17 @@ int attention_impl(const void* q_, const void* k_, const void* v_, void* out_, i
   E* aR = (E*)(ws + w.aR);
   float* cR = (float*)(ws + w.cR);
   const float s = 1.0f / sqrtf((float)d);
-  const float cr_min = g_cr_min;
-  const int cr_control = g_cr_control, cl_control = g_cl_control;
-  const float cl_value = std::isnan(g_cl_value) ? -logf((float)dm.b) : g_cl_value;
+  const float cr_min = cfg.cr_min;
+  const int cr_control = cfg.cr_control, cl_control = cfg.cl_control;
+  const float cl_value = std::isnan(cfg.cl_value) ? -logf((float)dm.b) : cfg.cl_value;
   // App. A: aR = Q, cR = 1, then `iters` times (R-update; L-update); y = R V and O = L y
   // ride on the last sweep.  Q carries 1/sqrt(d) through row_scale / q_scale.
-  g_n_phases = 0;
+  if (g_timing) g_n_phases = 0;
   for (int sweep = 0; sweep < iters; ++sweep) {
     const bool last = sweep == iters - 1;
     phase_mark(st, last ? "r_update_last" : "r_update");
     rc = r_update_any<E>(sweep == 0 ? q : aR, sweep == 0 ? nullptr : cR, k, last ? v : nullptr, aL, cL,
-                         last ? y : nullptr, nullptr, dm, s, cr_min, st);
+                         last ? y : nullptr, nullptr, dm, s, cr_min, cfg, st);
     if (rc) return rc;
     // manual control (App. "Manual Control of Monarch Parameters"): overwrite the term just produced,
     // for key frame 0 (the head's first b entries) or for all frames
@@ -349,7 +398,7 @@ int r_update_impl(const void* aR, const float* cR, const void* k, const void* v,
   int rc = make_dims(B, heads, T, Hs, Ws, d, &dm);
   if (rc) return rc;
   return r_update_any<E>((const E*)aR, cR, (const E*)k, (const E*)v, (E*)aL, cL, (E*)y, lse, dm, row_scale, cr_min,
-                         (hipStream_t)stream);
+                         current_settings(), (hipStream_t)stream);
 }
 
 template <typename E>
@@ -383,7 +432,7 @@ int first_frame_impl(const void* q, const void* k, const void* v, void* out, flo
   if (sizeof(E) == 2 && flash_supported(dm)) {
     sb = align_up(first_frame_flash_scratch_bytes(dm, nrows));
     if (sb > 0) {
-      scratch = get_workspace(sb, &rc);
+      scratch = get_workspace(sb, &rc, nullptr, 0, (hipStream_t)stream);
       if (!scratch) return rc;
     }
   }
@@ -403,7 +452,8 @@ int entropy_bwd_impl(const void* q, const float* cR, const void* k, const void* 
   int rc = make_dims(B, heads, T, Hs, Ws, d, &dm);
   if (rc) return rc;
   const bool mfma = sizeof(E) == 2 && entropy_bwd_mfma_supported(dm);
-  void* scratch = get_workspace(align_up(mfma ? entropy_bwd_mfma_scratch_bytes(dm) : entropy_bwd_scratch_bytes(dm)), &rc);
+  void* scratch = get_workspace(align_up(mfma ? entropy_bwd_mfma_scratch_bytes(dm) : entropy_bwd_scratch_bytes(dm)), &rc,
+                                nullptr, 0, (hipStream_t)stream);
   if (!scratch) return rc;
   if (mfma) {
     hipError_t e = launch_entropy_bwd_mfma((const bf16_t*)q, cR, (const bf16_t*)k, (const bf16_t*)v, (const bf16_t*)o,
@@ -529,11 +579,69 @@ int vmonarch_shutdown(void) {
 
 int vmonarch_attention(const void* q, const void* k, const void* v, void* out, int B, int heads, int T, int Hs, int Ws,
                        int d, int iters, int recompute, void* stream) {
-  return attention_impl<bf16_t>(q, k, v, out, B, heads, T, Hs, Ws, d, iters, recompute, stream);
+  return attention_impl<bf16_t>(q, k, v, out, B, heads, T, Hs, Ws, d, iters, recompute, current_settings(), stream);
 }
 int vmonarch_attention_f32(const void* q, const void* k, const void* v, void* out, int B, int heads, int T, int Hs,
                            int Ws, int d, int iters, int recompute, void* stream) {
-  return attention_impl<float>(q, k, v, out, B, heads, T, Hs, Ws, d, iters, recompute, stream);
+  return attention_impl<float>(q, k, v, out, B, heads, T, Hs, Ws, d, iters, recompute, current_settings(), stream);
+}
+
+static int settings_from_options(const vmonarch_options* o, Settings* cfg) {
+  if (o == nullptr) return fail(VMONARCH_ERR_INVALID_ARG, "null options");
+  if (o->struct_bytes != sizeof(vmonarch_options))
+    return fail(VMONARCH_ERR_INVALID_ARG, "options.struct_bytes is %u, this library's vmonarch_options has %zu bytes",
+                o->struct_bytes, sizeof(vmonarch_options));
+  if (!(o->cr_min >= 0.f)) return fail(VMONARCH_ERR_INVALID_ARG, "options.cr_min must be >= 0");
+  if (o->entropy_mode != VMONARCH_ENTROPY_ONLINE && o->entropy_mode != VMONARCH_ENTROPY_IDENTITY)
+    return fail(VMONARCH_ERR_INVALID_ARG, "unknown options.entropy_mode %d", o->entropy_mode);
+  if (o->flash_variant != 0 && o->flash_variant != 1) return fail(VMONARCH_ERR_INVALID_ARG, "options.flash_variant is 0 or 1");
+  if (o->cr_control < VMONARCH_CONTROL_NONE || o->cr_control > VMONARCH_CONTROL_ALL_FRAMES ||
+      o->cl_control < VMONARCH_CONTROL_NONE || o->cl_control > VMONARCH_CONTROL_ALL_FRAMES)
+    return fail(VMONARCH_ERR_INVALID_ARG, "options control modes are 0 (none), 1 (first frame), 2 (all frames)");
+  if (std::isinf(o->cl_value)) return fail(VMONARCH_ERR_INVALID_ARG, "options.cl_value must be finite, or NaN for -log(b)");
+  if ((o->workspace == nullptr) != (o->workspace_bytes == 0))
+    return fail(VMONARCH_ERR_INVALID_ARG, "options.workspace and workspace_bytes must both be zero or both non-zero");
+  if (((uintptr_t)o->workspace & 255) != 0) return fail(VMONARCH_ERR_INVALID_ARG, "options.workspace must be 256-byte aligned");
+  cfg->cr_min = o->cr_min;
+  cfg->entropy_mode = o->entropy_mode;
+  cfg->fused_apply = o->fused_apply != 0;
+  cfg->flash_variant = o->flash_variant;
+  cfg->cr_control = o->cr_control;
+  cfg->cl_control = o->cl_control;
+  cfg->cl_value = o->cl_value;
+  cfg->workspace = o->workspace;
+  cfg->workspace_bytes = o->workspace_bytes;
+  return VMONARCH_OK;
+}
+
+int vmonarch_options_init(vmonarch_options* options) {
+  if (options == nullptr) return fail(VMONARCH_ERR_INVALID_ARG, "null options");
+  options->struct_bytes = (uint32_t)sizeof(vmonarch_options);
+  options->cr_min = 0.1f;
+  options->entropy_mode = VMONARCH_ENTROPY_ONLINE;
+  options->fused_apply = 1;
+  options->flash_variant = 0;
+  options->cr_control = VMONARCH_CONTROL_NONE;
+  options->cl_control = VMONARCH_CONTROL_NONE;
+  options->cl_value = NAN;
+  options->workspace = nullptr;
+  options->workspace_bytes = 0;
+  return VMONARCH_OK;
+}
+
+int vmonarch_attention_ex(const void* q, const void* k, const void* v, void* out, int B, int heads, int T, int Hs, int Ws,
+                          int d, int iters, int recompute, const vmonarch_options* options, void* stream) {
+  Settings cfg;
+  int rc = settings_from_options(options, &cfg);
+  if (rc) return rc;
+  return attention_impl<bf16_t>(q, k, v, out, B, heads, T, Hs, Ws, d, iters, recompute, cfg, stream);
+}
+int vmonarch_attention_ex_f32(const void* q, const void* k, const void* v, void* out, int B, int heads, int T, int Hs,
+                              int Ws, int d, int iters, int recompute, const vmonarch_options* options, void* stream) {
+  Settings cfg;
+  int rc = settings_from_options(options, &cfg);
+  if (rc) return rc;
+  return attention_impl<float>(q, k, v, out, B, heads, T, Hs, Ws, d, iters, recompute, cfg, stream);
 }
 
 int vmonarch_r_update(const void* aR, const float* cR, const void* k, const void* v, void* aL_out, float* cL_out,

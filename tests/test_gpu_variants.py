@@ -24,7 +24,7 @@ def _tol(bf16):
     return (U.BF16_REL_L2, U.BF16_MAX_ABS) if bf16 else (1e-4, 1e-4)
 
 
-def _within(got, res, abs_tol, bf16, q_scaled=None):
+def _within(got, res, abs_tol, bf16, q_scaled=None, recomputed_frame=True):
     """Element-wise bound against an oracle result `res` (kept factors).  In the bf16 path an output element
     O[j,i] = sum_k L[j,k] y[k] carries three roundings: of every y[k] when it is stored (half an ulp, at most
     2^-8 |y[k]|), of every weight L[j,k] as a matrix operand (2^-9 relative) and of the result (at most 2^-8 |O|):
@@ -44,7 +44,8 @@ def _within(got, res, abs_tol, bf16, q_scaled=None):
     shift = 2.0 * du.max(axis=2).T                                                       # [j, i]
     bound = (2.0 ** -8 + 2.0 ** -9 + shift[:, :, None]) * spread + 2.0 ** -8 * np.abs(res["O"])
     bound = np.maximum(abs_tol, bound).reshape(T * s_, d)
-    bound[:s_] = abs_tol     # the recomputed frame
+    if recomputed_frame:
+        bound[:s_] = abs_tol
     ratio = np.abs(got - ref) / bound
     w = np.unravel_index(np.argmax(ratio), ratio.shape)
     print(f"  worst element: token {w[0]} (frame {w[0] // s_}) channel {w[1]}: got {got[w]:.5f} ref {ref[w]:.5f} "
@@ -161,3 +162,50 @@ def test_variant_arguments_are_validated(env):
     with pytest.raises(binding.VMonarchError):
         binding.sink_average(x, x, x, 2, 2, 2, x)
     assert binding.get_manual_control()[:2] == (0, 0)
+
+
+def test_per_call_options_on_two_streams(env):
+    """vmonarch_attention_ex: two calls with different settings and their own workspaces, enqueued back to back on
+    two streams (several rounds, so that they overlap in time), each against its own variant of the oracle; the
+    process-wide settings stay untouched."""
+    torch, binding, dev = env
+    T, Hs, Ws, d, heads, iters = 9, 9, 11, 128, 2, 2
+    b = Hs * Ws
+    data = U.structured_heads(T, Hs, Ws, d, 35, heads, True)
+    tq, tk, tv = (U.to_device([h[i] for h in data], torch, dev) for i in range(3))
+    opt_a = binding.default_options()                      # plain: clamp 0.1, online entropy, first-frame recomputation
+    opt_b = binding.default_options()                      # manual control of both terms, no clamp, other kernels
+    opt_b.cr_control, opt_b.cl_control, opt_b.cl_value = 1, 1, -2.5
+    opt_b.cr_min = 0.0
+    opt_b.entropy_mode = binding.ENTROPY_IDENTITY
+    opt_b.flash_variant = 1
+    nbytes = binding.workspace_bytes(1, heads, T, Hs, Ws, d, iters, True, 2)
+    ws_a = torch.empty(nbytes, dtype=torch.uint8, device=dev)
+    ws_b = torch.empty(nbytes, dtype=torch.uint8, device=dev)
+    out_a, out_b = torch.empty_like(tq), torch.empty_like(tq)
+    s_a, s_b = torch.cuda.Stream(), torch.cuda.Stream()
+    torch.cuda.synchronize()
+    for _ in range(4):
+        with torch.cuda.stream(s_a):
+            binding.attention_ex(tq, tk, tv, T, Hs, Ws, iters, True, opt_a, out=out_a, workspace=ws_a)
+        with torch.cuda.stream(s_b):
+            binding.attention_ex(tq, tk, tv, T, Hs, Ws, iters, False, opt_b, out=out_b, workspace=ws_b)
+    torch.cuda.synchronize()
+    assert binding.get_manual_control()[:2] == (0, 0) and binding.get_cr_min() == pytest.approx(0.1)
+    got_a, got_b = U.from_device(out_a), U.from_device(out_b)
+    for h in range(heads):
+        q64, k64, v64 = (U.to_f64(x) for x in data[h])
+        res_a = O.monarch_attention(q64, k64, v64, T, b, iters, recompute=True, keep_factors=True)
+        res_b = O.monarch_attention(q64, k64, v64, T, b, iters, recompute=False, cr_min=0.0, cr_control=1, cl_control=1,
+                                    cl_value=-2.5, keep_factors=True)
+        qs = (q64 / math.sqrt(d)).reshape(T, b, d)
+        for tag, got, res, rec in (("plain", got_a[h], res_a, True), ("controlled", got_b[h], res_b, False)):
+            ref = res["O"].reshape(T * b, d)
+            ok, ratio = _within(got, res, U.BF16_MAX_ABS, True, qs, recomputed_frame=rec)
+            print(f"options {tag} head {h}: rel {U.rel_l2(got, ref):.2e} max {U.max_abs(got, ref):.2e} worst/bound {ratio:.2f}")
+            assert U.rel_l2(got, ref) <= U.BF16_REL_L2 and ok
+        assert U.rel_l2(res_a["O"], res_b["O"]) > 5e-2      # the two settings really differ
+    # a workspace that is too small is refused before anything is launched
+    opt_a.workspace_bytes = 256
+    with pytest.raises(binding.VMonarchError):
+        binding.attention_ex(tq, tk, tv, T, Hs, Ws, iters, True, opt_a)
