@@ -246,6 +246,22 @@ int vmonarch_recompute_rows_f32(const void* q, const void* k, const void* v, voi
                                 void* stream);
 
 /*
+ * Recomputation of an arbitrary set of tokens (the paper's closing remark: recomputation of
+ * specific tokens in general, not only of the first frame): for every r < n_rows and every head,
+ *     out[rows_dev[r]] = softmax(Q[rows_dev[r]] K^T / sqrt(d)) V     over all N keys,
+ * the listed query rows gathered when they are loaded and the results scattered when they are
+ * stored (no staging copy).  rows_dev: DEVICE int32[n_rows], row numbers within a head, the same
+ * list for every (batch, head); any order; n_rows >= 1.  The host cannot see the list: an entry
+ * outside [0, N) is skipped on the device (nothing is read or written for it); a row listed twice is
+ * computed twice and stored twice with the same value.  All other rows of `out` are left as they are.
+ * Uses the workspace like vmonarch_recompute_rows.
+ */
+int vmonarch_recompute_tokens(const void* q, const void* k, const void* v, void* out, const int32_t* rows_dev,
+                              long long n_rows, int B, int heads, int T, int Hs, int Ws, int d, void* stream);
+int vmonarch_recompute_tokens_f32(const void* q, const void* k, const void* v, void* out, const int32_t* rows_dev,
+                                  long long n_rows, int B, int heads, int T, int Hs, int Ws, int d, void* stream);
+
+/*
  * vmonarch_recompute_rows (bf16) for callers that cannot allocate device memory: code under HIP
  * graph capture, tight serving loops, harnesses that forbid hipMalloc.  Same arguments, same
  * kernels, same results; the partial results of the key ranges go to a buffer built into the

@@ -35,6 +35,7 @@ EXPORTS = [
     "vmonarch_set_fused_apply", "vmonarch_get_fused_apply", "vmonarch_recompute_rows_noalloc",
     "vmonarch_set_flash_variant", "vmonarch_get_flash_variant",
     "vmonarch_options_init", "vmonarch_attention_ex", "vmonarch_attention_ex_f32",
+    "vmonarch_recompute_tokens", "vmonarch_recompute_tokens_f32",
 ]
 
 
@@ -86,6 +87,8 @@ def lib() -> ctypes.CDLL:
             getattr(L, name).argtypes = [c_void_p] * 4 + dims + [c_void_p]
         for name in ("vmonarch_entropy_attention_bwd", "vmonarch_entropy_attention_bwd_f32"):
             getattr(L, name).argtypes = [c_void_p] * 12 + dims + [c_float, c_float, c_void_p]
+        for name in ("vmonarch_recompute_tokens", "vmonarch_recompute_tokens_f32"):
+            getattr(L, name).argtypes = [c_void_p] * 5 + [ctypes.c_longlong] + dims + [c_void_p]
         L.vmonarch_options_init.argtypes = [ctypes.POINTER(Options)]
         for name in ("vmonarch_attention_ex", "vmonarch_attention_ex_f32"):
             getattr(L, name).argtypes = [c_void_p] * 4 + dims + [c_int, c_int, ctypes.POINTER(Options), c_void_p]
@@ -288,6 +291,16 @@ def set_flash_variant(variant: int):
 
 def get_flash_variant() -> int:
     return int(lib().vmonarch_get_flash_variant())
+
+
+def recompute_tokens(q, k, v, T, Hs, Ws, out, rows):
+    """Overwrites the rows listed in `rows` (int32 CUDA tensor, row numbers within a head) of every head of `out`
+    with exact attention over all keys."""
+    B, heads, N, d = q.shape
+    assert rows.dtype == torch.int32 and rows.is_cuda and rows.is_contiguous()
+    fn = getattr(lib(), "vmonarch_recompute_tokens" + _suffix(q))
+    _check(fn(_ptr(q), _ptr(k), _ptr(v), _ptr(out), _ptr(rows), rows.numel(), B, heads, T, Hs, Ws, d, _stream()))
+    return out
 
 
 def recompute_rows_noalloc(q, k, v, T, Hs, Ws, out, row_begin, row_count):

@@ -275,21 +275,21 @@ int l_update_any<bf16_t>(const bf16_t* q, const bf16_t* aL, const float* cL, con
 
 template <typename E>
 int first_frame_any(const E* q, const E* k, const E* v, E* out, float* lse, void* scratch, size_t scratch_bytes,
-                    const Dims& dm, int nrows, hipStream_t st);
+                    const Dims& dm, int nrows, const int* rows, hipStream_t st);
 template <>
 int first_frame_any<float>(const float* q, const float* k, const float* v, float* out, float* lse, void*, size_t,
-                           const Dims& dm, int nrows, hipStream_t st) {
-  hipError_t e = launch_first_frame_generic<float>(q, k, v, out, lse, dm, nrows, st);
+                           const Dims& dm, int nrows, const int* rows, hipStream_t st) {
+  hipError_t e = launch_first_frame_generic<float>(q, k, v, out, lse, dm, nrows, rows, st);
   return e == hipSuccess ? VMONARCH_OK : hip_fail(e, "first_frame (plain-ALU f32) launch");
 }
 template <>
 int first_frame_any<bf16_t>(const bf16_t* q, const bf16_t* k, const bf16_t* v, bf16_t* out, float* lse, void* scratch,
-                            size_t scratch_bytes, const Dims& dm, int nrows, hipStream_t st) {
+                            size_t scratch_bytes, const Dims& dm, int nrows, const int* rows, hipStream_t st) {
   hipError_t e;
   if (flash_supported(dm))
-    e = launch_first_frame_flash(q, k, v, out, lse, scratch, scratch_bytes, dm, nrows, st);
+    e = launch_first_frame_flash(q, k, v, out, lse, scratch, scratch_bytes, dm, nrows, rows, st);
   else
-    e = launch_first_frame_generic<bf16_t>(q, k, v, out, lse, dm, nrows, st);
+    e = launch_first_frame_generic<bf16_t>(q, k, v, out, lse, dm, nrows, rows, st);
   return e == hipSuccess ? VMONARCH_OK : hip_fail(e, "first_frame (bf16) launch");
 }
 
@@ -380,7 +380,7 @@ int attention_impl(const void* q_, const void* k_, const void* v_, void* out_, i
     if (rc) return rc;
   } else if (recompute) {
     phase_mark(st, "first_frame");
-    rc = first_frame_any<E>(q, k, v, out, nullptr, ws + w.ff, w.total - w.ff, dm, dm.b, st);
+    rc = first_frame_any<E>(q, k, v, out, nullptr, ws + w.ff, w.total - w.ff, dm, dm.b, nullptr, st);
     if (rc) return rc;
   }
   phase_mark(st, nullptr);
@@ -438,7 +438,31 @@ int first_frame_impl(const void* q, const void* k, const void* v, void* out, flo
   }
   // the kernels index query rows from the pointers they are given: hand them the first row of the range
   return first_frame_any<E>((const E*)q + row_begin * d, (const E*)k, (const E*)v, (E*)out + row_begin * d,
-                            lse ? lse + row_begin : nullptr, scratch, sb, dm, nrows, (hipStream_t)stream);
+                            lse ? lse + row_begin : nullptr, scratch, sb, dm, nrows, nullptr, (hipStream_t)stream);
+}
+
+// Exact attention of a list of rows (the same list for every head).
+template <typename E>
+int recompute_tokens_impl(const void* q, const void* k, const void* v, void* out, const int32_t* rows, long long n_rows,
+                          int B, int heads, int T, int Hs, int Ws, int d, void* stream) {
+  if (!q || !k || !v || !out || !rows) return fail(VMONARCH_ERR_INVALID_ARG, "null pointer");
+  Dims dm;
+  int rc = make_dims(B, heads, T, Hs, Ws, d, &dm);
+  if (rc) return rc;
+  if (n_rows < 1 || n_rows > 0x7fffffffLL / 2)
+    return fail(VMONARCH_ERR_INVALID_ARG, "n_rows=%lld must lie in [1, 2^30)", n_rows);
+  const int nrows = (int)n_rows;
+  void* scratch = nullptr;
+  size_t sb = 0;
+  if (sizeof(E) == 2 && flash_supported(dm)) {
+    sb = align_up(first_frame_flash_scratch_bytes(dm, nrows));
+    if (sb > 0) {
+      scratch = get_workspace(sb, &rc, nullptr, 0, (hipStream_t)stream);
+      if (!scratch) return rc;
+    }
+  }
+  return first_frame_any<E>((const E*)q, (const E*)k, (const E*)v, (E*)out, nullptr, scratch, sb, dm, nrows, rows,
+                            (hipStream_t)stream);
 }
 
 template <typename E>
@@ -710,6 +734,15 @@ int vmonarch_recompute_rows_f32(const void* q, const void* k, const void* v, voi
   return first_frame_impl<float>(q, k, v, out, nullptr, B, heads, T, Hs, Ws, d, row_begin, row_count, stream);
 }
 
+int vmonarch_recompute_tokens(const void* q, const void* k, const void* v, void* out, const int32_t* rows_dev,
+                              long long n_rows, int B, int heads, int T, int Hs, int Ws, int d, void* stream) {
+  return recompute_tokens_impl<bf16_t>(q, k, v, out, rows_dev, n_rows, B, heads, T, Hs, Ws, d, stream);
+}
+int vmonarch_recompute_tokens_f32(const void* q, const void* k, const void* v, void* out, const int32_t* rows_dev,
+                                  long long n_rows, int B, int heads, int T, int Hs, int Ws, int d, void* stream) {
+  return recompute_tokens_impl<float>(q, k, v, out, rows_dev, n_rows, B, heads, T, Hs, Ws, d, stream);
+}
+
 int vmonarch_recompute_rows_noalloc(const void* q, const void* k, const void* v, void* out, int B, int heads, int T,
                                     int Hs, int Ws, int d, long long row_begin, long long row_count, void* stream) {
   if (!q || !k || !v || !out) return fail(VMONARCH_ERR_INVALID_ARG, "null tensor pointer");
@@ -736,7 +769,7 @@ int vmonarch_recompute_rows_noalloc(const void* q, const void* k, const void* v,
   }
   // every partial the merge reads is written by the key-range pass of the same call: nothing to clear
   return first_frame_any<bf16_t>((const bf16_t*)q + row_begin * d, (const bf16_t*)k, (const bf16_t*)v,
-                                 (bf16_t*)out + row_begin * d, nullptr, sp, sb, dm, nrows, (hipStream_t)stream);
+                                 (bf16_t*)out + row_begin * d, nullptr, sp, sb, dm, nrows, nullptr, (hipStream_t)stream);
 }
 
 int vmonarch_sink_average(const void* q, const void* k, const void* v, void* out, int B, int heads, int T, int Hs,

@@ -76,7 +76,7 @@ hipError_t launch_l_update_generic(const E* q, const E* aL, const float* cL, con
                                    E* out, const Dims& dm, float q_scale, hipStream_t st);
 template <typename E>
 hipError_t launch_first_frame_generic(const E* q, const E* k, const E* v, E* out, float* lse, const Dims& dm,
-                                      int nrows, hipStream_t st);
+                                      int nrows, const int* rows, hipStream_t st);
 hipError_t launch_permute_tokens(const void* in, void* out, const Dims& dm, int row_bytes, int to_pos_major,
                                  hipStream_t st);
 // out <- (out + softmax(q K_F1^T / sqrt(d)) V_F1) / 2 for every token, K_F1 / V_F1 the head's first b rows
@@ -122,8 +122,11 @@ hipError_t launch_r_update_flash2(const bf16_t* aR, const float* cR, const bf16_
                                   int entropy_mode, hipStream_t st);
 // exact attention of nrows query rows per head (starting where q / out / lse point) over all N keys
 size_t first_frame_flash_scratch_bytes(const Dims& dm, int nrows);
+// rows (device, may be null): a list of nrows row numbers within a head, used for every head; q / out / lse then
+// point at row 0; entries outside [0, N) are skipped
 hipError_t launch_first_frame_flash(const bf16_t* q, const bf16_t* k, const bf16_t* v, bf16_t* out, float* lse,
-                                    void* scratch, size_t scratch_bytes, const Dims& dm, int nrows, hipStream_t st);
+                                    void* scratch, size_t scratch_bytes, const Dims& dm, int nrows, const int* rows,
+                                    hipStream_t st);
 
 hipError_t launch_sink_average_flash(const bf16_t* q, const bf16_t* k, const bf16_t* v, bf16_t* out, const Dims& dm,
                                      hipStream_t st);

@@ -124,17 +124,26 @@ __global__ void __launch_bounds__(64 * NW) flash_kernel(FlashParams P) {
   // ---- queries: B operand of S^T = K Q^T, kept in registers -------------------------
   bf16x8 qreg[QT][KS];
   float sc[QT];
-  int qrow[QT];
+  int qrow[QT];   // row within the problem's list of query rows
+  int grow[QT];   // the row of the problem it stands for (the same unless a row list is given)
   bool qvalid[QT];
 #pragma unroll
   for (int qt = 0; qt < QT; ++qt) {
     int r = qb * BQ + wave * (32 * QT) + qt * 32 + ql;
     qvalid[qt] = r < P.nq;
     qrow[qt] = qvalid[qt] ? r : P.nq - 1;
-    const bf16_t* qp = P.q + (qrow0 + qrow[qt]) * D + 8 * g;
+    grow[qt] = qrow[qt];
+    if (P.q_index != nullptr) {
+      // a listed row; an entry that does not name a row of the head is skipped (read as row 0, never stored)
+      const int gi = P.q_index[qrow[qt]];
+      const bool inside = gi >= 0 && gi < P.q_index_limit;
+      qvalid[qt] = qvalid[qt] && inside;
+      grow[qt] = inside ? gi : 0;
+    }
+    const bf16_t* qp = P.q + (qrow0 + grow[qt]) * D + 8 * g;
 #pragma unroll
     for (int ks = 0; ks < KS; ++ks) qreg[qt][ks] = *reinterpret_cast<const bf16x8*>(qp + 16 * ks);
-    float c = P.cR ? P.cR[qrow0 + qrow[qt]] : 1.0f;
+    float c = P.cR ? P.cR[qrow0 + grow[qt]] : 1.0f;
     c = fmaxf(c, P.cr_min);
     sc[qt] = P.row_scale * LOG2E / c;
   }
@@ -333,7 +342,7 @@ __global__ void __launch_bounds__(64 * NW) flash_kernel(FlashParams P) {
   for (int qt = 0; qt < QT; ++qt) {
     const float lt = ltil[qt] + __shfl_xor(ltil[qt], 32);
     const float inv = lt > 0.f ? 1.0f / lt : 0.f;
-    const long long row = qrow0 + qrow[qt];
+    const long long row = qrow0 + grow[qt];
     if (!SPLIT) {
       if (P.lse != nullptr && qvalid[qt] && g == 0) P.lse[row] = LN2 * (msc[qt] + __log2f(lt));
       if (ENT == 1) {
@@ -400,9 +409,15 @@ __global__ void __launch_bounds__(64 * NW) flash_kernel(FlashParams P) {
       const int lr = ps * RPI + lane / CH;  // row within the wave's block
       const int pc = lane % CH;
       const int lc = pc ^ swz(lr);
-      if (row_first + lr < P.nq) {
+      int orow = row_first + lr;
+      bool ovalid = orow < P.nq;
+      if (P.q_index != nullptr && ovalid) {
+        orow = P.q_index[orow];
+        ovalid = orow >= 0 && orow < P.q_index_limit;
+      }
+      if (ovalid) {
         uint4 w = *reinterpret_cast<const uint4*>(stage + lr * ROW_BYTES + pc * 16);
-        uint4* gp = reinterpret_cast<uint4*>(dst + (qrow0 + row_first + lr) * D + lc * 8);
+        uint4* gp = reinterpret_cast<uint4*>(dst + (qrow0 + orow) * D + lc * 8);
         if (P.blend) w = average_bf16x8(w, *gp);
         *gp = w;
       }
@@ -424,12 +439,17 @@ __device__ __forceinline__ uint4 average_bf16x8(uint4 a, uint4 b) {
 __global__ void __launch_bounds__(128) merge_splits_kernel(const float* __restrict__ part_o,
                                                            const float* __restrict__ part_lse, bf16_t* __restrict__ out,
                                                            float* __restrict__ lse, int nsplit, long long rows_per_split,
-                                                           int nq, long long out_rows_per_problem) {
+                                                           int nq, long long out_rows_per_problem,
+                                                           const int* __restrict__ q_index, int q_index_limit) {
   const int D = blockDim.x;        // one thread per channel
   const long long r = blockIdx.x;  // problem * nq + row
   const int c = threadIdx.x;       // channel
   const long long prob = r / nq;
-  const long long row = r - prob * nq;
+  long long row = r - prob * nq;
+  if (q_index != nullptr) {
+    row = q_index[row];
+    if (row < 0 || row >= q_index_limit) return;  // not a row of the head: skipped
+  }
   float mx = -INFINITY;
   for (int s = 0; s < nsplit; ++s) mx = fmaxf(mx, part_lse[s * rows_per_split + r]);
   float wsum = 0.f, acc = 0.f;
@@ -540,8 +560,11 @@ size_t first_frame_flash_scratch_bytes(const Dims& dm, int nrows) {
 // q, out and lse point at the first row to recompute of head 0 (rows of later heads sit N rows
 // further on, like everything else); k and v at the heads' first tokens.
 hipError_t launch_first_frame_flash(const bf16_t* q, const bf16_t* k, const bf16_t* v, bf16_t* out, float* lse,
-                                    void* scratch, size_t scratch_bytes, const Dims& dm, int nrows, hipStream_t st) {
+                                    void* scratch, size_t scratch_bytes, const Dims& dm, int nrows, const int* row_list,
+                                    hipStream_t st) {
   FlashParams P = {};
+  P.q_index = row_list;  // null: the nrows rows that follow q / out / lse; else: rows[r] of every head, q / out / lse at row 0
+  P.q_index_limit = (int)dm.N;
   const int ns = first_frame_splits(dm, nrows);
   P.q = q; P.cR = nullptr; P.k = k; P.v = v; P.outk = nullptr; P.outv = out; P.cl = nullptr;
   P.lse = lse;  // written by the kernel itself when one key range covers everything, else by the merge
@@ -569,7 +592,7 @@ hipError_t launch_first_frame_flash(const bf16_t* q, const bf16_t* k, const bf16
   hipError_t e = d128 ? launch_flash<128, false, true, 0, true>(P, st) : launch_flash<64, false, true, 0, true>(P, st);
   if (e != hipSuccess) return e;
   hipLaunchKernelGGL(merge_splits_kernel, dim3((unsigned)((long long)dm.BH * nrows)), dim3(dm.d), 0, st, P.part_o,
-                     P.part_lse, out, lse, ns, (long long)dm.BH * nrows, nrows, dm.N);
+                     P.part_lse, out, lse, ns, (long long)dm.BH * nrows, nrows, dm.N, row_list, (int)dm.N);
   return hipGetLastError();
 }
 

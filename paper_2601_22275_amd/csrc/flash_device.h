@@ -45,6 +45,9 @@ struct FlashParams {
   float row_scale;
   float cr_min;
   int blend;            // outv <- (outv + result) / 2 instead of outv <- result
+  const int* q_index;   // flash_kernel: query row r of a problem is row q_index[r] of it (null: row r); entries
+                        // outside [0, q_index_limit) are skipped
+  int q_index_limit;
   int own_tile_first;   // flash2: queries and keys are the same rows (R-update): start the key loop at the query block's own tile
 };
 

@@ -130,11 +130,16 @@ template <typename E>
 __global__ void __launch_bounds__(64) first_frame_generic_kernel(const E* __restrict__ q, const E* __restrict__ k,
                                                                  const E* __restrict__ v, E* __restrict__ out,
                                                                  float* __restrict__ lse, int T, int b, int d,
-                                                                 float scale) {
+                                                                 float scale, const int* __restrict__ rows) {
   __shared__ float sq[kMaxD];
   __shared__ float sp[64];
-  const int i = blockIdx.x, bh = blockIdx.y;
+  int i = blockIdx.x;
+  const int bh = blockIdx.y;
   const long long N = (long long)T * b;
+  if (rows != nullptr) {
+    i = rows[i];
+    if (i < 0 || i >= N) return;  // not a row of the head: skipped (uniform over the workgroup)
+  }
   const long long head0 = (long long)bh * N;
   attend_row<E, false, true>(q + (head0 + i) * d, scale, k + head0 * d, v + head0 * d, N, d, nullptr,
                              out + (head0 + i) * d, nullptr, lse ? lse + head0 + i : nullptr, sq, sp);
@@ -318,10 +323,10 @@ hipError_t launch_l_update_generic(const E* q, const E* aL, const float* cL, con
 
 template <typename E>
 hipError_t launch_first_frame_generic(const E* q, const E* k, const E* v, E* out, float* lse, const Dims& dm,
-                                      int nrows, hipStream_t st) {
-  dim3 grid(nrows, dm.BH);  // q, out, lse point at the first row to recompute of head 0
+                                      int nrows, const int* rows, hipStream_t st) {
+  dim3 grid(nrows, dm.BH);  // q, out, lse point at the first row to recompute of head 0 (row 0 with a row list)
   hipLaunchKernelGGL((first_frame_generic_kernel<E>), grid, dim3(64), 0, st, q, k, v, out, lse, dm.T, dm.b, dm.d,
-                     1.0f / sqrtf((float)dm.d));
+                     1.0f / sqrtf((float)dm.d), rows);
   return hipGetLastError();
 }
 
@@ -364,9 +369,9 @@ template hipError_t launch_l_update_generic<float>(const float*, const float*, c
 template hipError_t launch_l_update_generic<bf16_t>(const bf16_t*, const bf16_t*, const float*, const bf16_t*, bf16_t*,
                                                     float*, bf16_t*, const Dims&, float, hipStream_t);
 template hipError_t launch_first_frame_generic<float>(const float*, const float*, const float*, float*, float*,
-                                                      const Dims&, int, hipStream_t);
+                                                      const Dims&, int, const int*, hipStream_t);
 template hipError_t launch_first_frame_generic<bf16_t>(const bf16_t*, const bf16_t*, const bf16_t*, bf16_t*, float*,
-                                                       const Dims&, int, hipStream_t);
+                                                       const Dims&, int, const int*, hipStream_t);
 template hipError_t launch_sink_average_generic<float>(const float*, const float*, const float*, float*, const Dims&,
                                                        hipStream_t);
 template hipError_t launch_sink_average_generic<bf16_t>(const bf16_t*, const bf16_t*, const bf16_t*, bf16_t*,

@@ -192,3 +192,15 @@ def test_headline_shape_ablation_variants_sampled_positions(env):
     for hi in range(len(heads)):
         ref = O.softmax_attention(wide[hi][0][rows], wide[hi][1], wide[hi][2], 1.0 / math.sqrt(wl.d))
         assert U.rel_l2(got[hi][rows], ref) <= U.BF16_REL_L2 and U.max_abs(got[hi][rows], ref) <= U.BF16_MAX_ABS
+    # an arbitrary subset of 3000 tokens spread over all frames, unsorted; everything else keeps the Monarch result
+    picked = rng.permutation(wl.N)[:3000]
+    subset = base.clone()
+    binding.recompute_tokens(tq, tk, tv, wl.T, wl.Hs, wl.Ws, subset, torch.from_numpy(picked.astype(np.int32)).to(dev))
+    keep = torch.ones(wl.N, dtype=torch.bool, device=dev)
+    keep[torch.from_numpy(picked).to(dev)] = False
+    assert torch.equal(subset[:, :, keep], base[:, :, keep])
+    check_rows = picked[:40]
+    got = subset.float().cpu().numpy()[0]
+    for hi in range(len(heads)):
+        ref = O.softmax_attention(wide[hi][0][check_rows], wide[hi][1], wide[hi][2], 1.0 / math.sqrt(wl.d))
+        assert U.rel_l2(got[hi][check_rows], ref) <= U.BF16_REL_L2 and U.max_abs(got[hi][check_rows], ref) <= U.BF16_MAX_ABS

@@ -366,6 +366,68 @@ def test_recompute_rows_any_range(env, T, Hs, Ws, d, dt, begin, count):
         binding.recompute_rows(tq, tk, tv, T, Hs, Ws, out, T * b - 3, 4)
 
 
+TOKEN_CASES = [
+    # T, Hs, Ws, d, dtype, kind of row list
+    (4, 4, 4, 32, "f32", "random"),
+    (3, 5, 5, 96, "bf16", "random"),          # plain-ALU bf16
+    (6, 9, 11, 128, "bf16", "sorted"),
+    (6, 9, 11, 128, "bf16", "unsorted"),
+    (6, 9, 11, 64, "bf16", "one"),
+    (5, 8, 8, 128, "bf16", "all"),
+    (5, 8, 8, 64, "bf16", "all-reversed"),
+    (20, 16, 16, 128, "bf16", "many"),        # several query blocks and key ranges, merged partial results
+    (6, 9, 11, 128, "bf16", "with-strays"),   # entries outside [0, N) are skipped on the device
+]
+
+
+@pytest.mark.parametrize("T,Hs,Ws,d,dt,kind", TOKEN_CASES)
+def test_recompute_tokens_any_subset(env, T, Hs, Ws, d, dt, kind):
+    """Exact attention for an arbitrary list of rows (gathered on load, scattered on store): sorted and unsorted
+    lists, one row, every row, a list long enough for several query blocks and key ranges; rows that are not
+    listed stay bit-identical; the range form of the same rows gives the same bits."""
+    torch, binding, dev = env
+    bf16 = dt == "bf16"
+    b, heads = Hs * Ws, 2
+    N = T * b
+    rng = np.random.default_rng(100 + T + d)
+    if kind == "one":
+        rows = np.array([N - 2])
+    elif kind == "all":
+        rows = np.arange(N)
+    elif kind == "all-reversed":
+        rows = np.arange(N)[::-1].copy()
+    elif kind == "many":
+        rows = rng.permutation(N)[:1500]
+    else:
+        rows = rng.permutation(N)[:max(3, N // 7)]
+        if kind == "sorted":
+            rows = np.sort(rows)
+    listed = rows.copy()
+    if kind == "with-strays":
+        listed = np.concatenate([rows[:5], [-1, N, 2 ** 31 - 1, -2 ** 31], rows[5:]])
+    data = U.structured_heads(T, Hs, Ws, d, 29, heads, bf16)
+    tq, tk, tv = (U.to_device([h[i] for h in data], torch, dev) for i in range(3))
+    torch.manual_seed(3)
+    base = torch.randn((1, heads, N, d), device=dev).to(tq.dtype)
+    out = base.clone()
+    trows = torch.from_numpy(listed.astype(np.int32)).to(dev)
+    binding.recompute_tokens(tq, tk, tv, T, Hs, Ws, out, trows)
+    got, base_np = U.from_device(out), U.from_device(base)
+    rel_tol, abs_tol = _tol(bf16)
+    untouched = np.setdiff1d(np.arange(N), rows)
+    for h in range(heads):
+        q64, k64, v64 = (U.to_f64(x) for x in data[h])
+        ref = O.softmax_attention(q64[rows], k64, v64, 1.0 / math.sqrt(d))
+        assert U.rel_l2(got[h][rows], ref) <= rel_tol and U.max_abs(got[h][rows], ref) <= abs_tol
+        assert np.array_equal(got[h][untouched], base_np[h][untouched])
+    if kind in ("all", "all-reversed"):
+        # the same rows as one contiguous range: identical arithmetic per row, identical bits
+        ranged = binding.recompute_rows(tq, tk, tv, T, Hs, Ws, base.clone(), 0, N)
+        assert torch.equal(ranged.view(torch.uint8), out.view(torch.uint8))
+    with pytest.raises(binding.VMonarchError):
+        binding.recompute_tokens(tq, tk, tv, T, Hs, Ws, out, trows[:0])
+
+
 @pytest.mark.parametrize("T,Hs,Ws,d,dt", [(4, 4, 4, 32, "f32"), (1, 3, 3, 128, "bf16"), (9, 7, 9, 128, "bf16"),
                                            (40, 16, 16, 64, "bf16")])
 def test_first_frame_log_sum_exp_output(env, T, Hs, Ws, d, dt):
