@@ -32,10 +32,10 @@
  *     options.workspace).  The vmonarch_set_* settings are process-wide and not synchronised: they
  *     are read when a call is made (a HIP graph captured from a call keeps what was set then);
  *     vmonarch_attention_ex carries them per call instead.
- *   - Sizes.  d <= 256, B*heads <= 65535, T <= 65535, N < 2^31 for every entry point.  bf16 with
- *     d == 128 or d == 64 runs on the MFMA kernels (any T, any Hs*Ws); other shapes and every
- *     `_f32` entry point run on slower plain-ALU kernels with the same results, whose temporal pass
- *     keeps a T x T block in LDS and therefore needs T <= 200 (VMONARCH_ERR_UNSUPPORTED beyond).
+ *   - Sizes.  d <= 256, B*heads <= 65535, T <= 65535, N < 2^31 for every entry point; no other
+ *     shape is refused.  bf16 with d == 128 or d == 64 runs on the MFMA kernels (the temporal factor
+ *     on a kernel of its own up to T = 128 and through the blocked-softmax kernel up to T = 8128);
+ *     other shapes and every `_f32` entry point run on slower plain-ALU kernels with the same results.
  *   - (T, Hs, Ws) only enter as m = T blocks of b = Hs*Ws tokens: a general Monarch split
  *     (m, b) of a sequence that is no video is T = m, Hs = 1, Ws = b.
  */
@@ -51,7 +51,7 @@ extern "C" {
 
 #define VMONARCH_OK 0
 #define VMONARCH_ERR_INVALID_ARG (-1) /* null pointer, non-positive size, iters < 1 */
-#define VMONARCH_ERR_UNSUPPORTED (-2) /* d > 256, a size whose index does not fit, T > 200 on the plain-ALU path */
+#define VMONARCH_ERR_UNSUPPORTED (-2) /* d > 256, or a size whose index does not fit (see "Sizes" above) */
 #define VMONARCH_ERR_WORKSPACE (-3)   /* caller workspace too small / allocation failed */
 #define VMONARCH_ERR_HIP (-4)         /* a HIP runtime call failed */
 

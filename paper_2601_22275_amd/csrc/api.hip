@@ -126,8 +126,16 @@ void* noalloc_scratch(int* err) {
 }
 
 struct WsLayout {
-  size_t aL, aR, y, cL, cR, ff, total;
+  size_t aL, aR, y, cL, cR, tl, ff, total;
 };
+
+// bf16 temporal factor with more frames than the one-workgroup-per-position kernel holds: the blocked-softmax
+// kernel takes it in two passes and keeps the rows' log-sum-exp in between
+bool temporal_needs_lse(const Dims& dm, int elem_bytes) {
+  if (elem_bytes == 2 && lpass_supported(dm)) return false;
+  if (elem_bytes == 2 && temporal_flash_supported(dm)) return true;
+  return l_update_generic_needs_lse(dm);  // plain-ALU kernels
+}
 
 WsLayout ws_layout(const Dims& dm, int iters, int recompute, int elem_bytes) {
   WsLayout w;
@@ -139,6 +147,7 @@ WsLayout ws_layout(const Dims& dm, int iters, int recompute, int elem_bytes) {
   w.cL = off; off += sc;
   w.aR = off; if (iters > 1) off += tok;
   w.cR = off; if (iters > 1) off += sc;
+  w.tl = off; if (iters > 1 && temporal_needs_lse(dm, elem_bytes)) off += sc;
   w.ff = off;
   if (recompute == VMONARCH_RECOMPUTE_FIRST_FRAME && elem_bytes == 2 && flash_supported(dm)) off += align_up(first_frame_flash_scratch_bytes(dm, dm.b));
   w.total = off;
@@ -249,26 +258,26 @@ int r_update_any<bf16_t>(const bf16_t* aR, const float* cR, const bf16_t* k, con
   return e == hipSuccess ? VMONARCH_OK : hip_fail(e, "r_update (bf16) launch");
 }
 
+// lse_scratch: BH * N floats, needed only when temporal_needs_lse() and the fitting form (y == null) is asked for
 template <typename E>
-int l_update_any(const E* q, const E* aL, const float* cL, const E* y, E* aR, float* cR, E* out, const Dims& dm,
-                 float q_scale, hipStream_t st);
+int l_update_any(const E* q, const E* aL, const float* cL, const E* y, E* aR, float* cR, E* out, float* lse_scratch,
+                 const Dims& dm, float q_scale, hipStream_t st);
 template <>
 int l_update_any<float>(const float* q, const float* aL, const float* cL, const float* y, float* aR, float* cR,
-                        float* out, const Dims& dm, float q_scale, hipStream_t st) {
-  if (dm.T > 200) return fail(VMONARCH_ERR_UNSUPPORTED, "plain-ALU L-update keeps a T x T block in LDS: T=%d > 200", dm.T);
-  hipError_t e = launch_l_update_generic<float>(q, aL, cL, y, aR, cR, out, dm, q_scale, st);
+                        float* out, float* lse_scratch, const Dims& dm, float q_scale, hipStream_t st) {
+  hipError_t e = launch_l_update_generic<float>(q, aL, cL, y, aR, cR, out, lse_scratch, dm, q_scale, st);
   return e == hipSuccess ? VMONARCH_OK : hip_fail(e, "l_update (plain-ALU f32) launch");
 }
 template <>
 int l_update_any<bf16_t>(const bf16_t* q, const bf16_t* aL, const float* cL, const bf16_t* y, bf16_t* aR, float* cR,
-                         bf16_t* out, const Dims& dm, float q_scale, hipStream_t st) {
+                         bf16_t* out, float* lse_scratch, const Dims& dm, float q_scale, hipStream_t st) {
   hipError_t e;
   if (lpass_supported(dm)) {
     e = launch_l_update_mfma(q, aL, cL, y, aR, cR, out, dm, q_scale, st);
+  } else if (temporal_flash_supported(dm)) {
+    e = launch_l_update_flash(q, aL, cL, y, aR, cR, out, lse_scratch, dm, q_scale, st);
   } else {
-    if (dm.T > 200)
-      return fail(VMONARCH_ERR_UNSUPPORTED, "plain-ALU L-update keeps a T x T block in LDS: T=%d > 200", dm.T);
-    e = launch_l_update_generic<bf16_t>(q, aL, cL, y, aR, cR, out, dm, q_scale, st);
+    e = launch_l_update_generic<bf16_t>(q, aL, cL, y, aR, cR, out, lse_scratch, dm, q_scale, st);
   }
   return e == hipSuccess ? VMONARCH_OK : hip_fail(e, "l_update (bf16) launch");
 }
@@ -366,7 +375,7 @@ int attention_impl(const void* q_, const void* k_, const void* v_, void* out_, i
     }
     phase_mark(st, last ? "l_update_last" : "l_update");
     rc = l_update_any<E>(q, aL, cL, last ? y : nullptr, last ? nullptr : aR, last ? nullptr : cR, last ? out : nullptr,
-                         dm, s, st);
+                         (float*)(ws + w.tl), dm, s, st);
     if (rc) return rc;
     if (!last && cr_control != VMONARCH_CONTROL_NONE) {
       hipError_t e = launch_fill_head_prefix(cR, 1.0f, cr_control == VMONARCH_CONTROL_ALL_FRAMES ? dm.N : dm.b, dm.N,
@@ -411,7 +420,12 @@ int l_update_impl(const void* q, const void* aL, const float* cL, const void* y,
   Dims dm;
   int rc = make_dims(B, heads, T, Hs, Ws, d, &dm);
   if (rc) return rc;
-  return l_update_any<E>((const E*)q, (const E*)aL, cL, (const E*)y, (E*)aR, cR, (E*)out, dm, q_scale,
+  float* lse_scratch = nullptr;
+  if (!fin && temporal_needs_lse(dm, (int)sizeof(E))) {
+    lse_scratch = (float*)get_workspace(align_up((size_t)dm.BH * dm.N * sizeof(float)), &rc, nullptr, 0, (hipStream_t)stream);
+    if (!lse_scratch) return rc;
+  }
+  return l_update_any<E>((const E*)q, (const E*)aL, cL, (const E*)y, (E*)aR, cR, (E*)out, lse_scratch, dm, q_scale,
                          (hipStream_t)stream);
 }
 

@@ -71,9 +71,12 @@ struct Dims {
 template <typename E>
 hipError_t launch_r_update_generic(const E* aR, const float* cR, const E* k, const E* v, E* aL, float* cL,
                                    E* y, float* lse, const Dims& dm, float row_scale, float cr_min, hipStream_t st);
+// lse_scratch (BH * N floats) is needed for the fitting form when l_update_generic_needs_lse(): more frames than the
+// kernel that keeps the T x T block in LDS can hold
+bool l_update_generic_needs_lse(const Dims& dm);
 template <typename E>
 hipError_t launch_l_update_generic(const E* q, const E* aL, const float* cL, const E* y, E* aR, float* cR,
-                                   E* out, const Dims& dm, float q_scale, hipStream_t st);
+                                   E* out, float* lse_scratch, const Dims& dm, float q_scale, hipStream_t st);
 template <typename E>
 hipError_t launch_first_frame_generic(const E* q, const E* k, const E* v, E* out, float* lse, const Dims& dm,
                                       int nrows, const int* rows, hipStream_t st);
@@ -127,6 +130,11 @@ size_t first_frame_flash_scratch_bytes(const Dims& dm, int nrows);
 hipError_t launch_first_frame_flash(const bf16_t* q, const bf16_t* k, const bf16_t* v, bf16_t* out, float* lse,
                                     void* scratch, size_t scratch_bytes, const Dims& dm, int nrows, const int* rows,
                                     hipStream_t st);
+
+// the temporal factor for any T <= 8128 through the same kernel (see flash.hip); lse_scratch: BH * N floats, fitting sweep only
+bool temporal_flash_supported(const Dims& dm);
+hipError_t launch_l_update_flash(const bf16_t* q, const bf16_t* aL, const float* cL, const bf16_t* y, bf16_t* aR, float* cR,
+                                 bf16_t* out, float* lse_scratch, const Dims& dm, float q_scale, hipStream_t st);
 
 hipError_t launch_sink_average_flash(const bf16_t* q, const bf16_t* k, const bf16_t* v, bf16_t* out, const Dims& dm,
                                      hipStream_t st);

@@ -32,7 +32,7 @@ namespace {
 __device__ __forceinline__ uint32_t average_bf16x2(uint32_t a, uint32_t b);
 __device__ __forceinline__ uint4 average_bf16x8(uint4 a, uint4 b);
 
-template <int D, bool OUT_K, bool OUT_V, int ENT, bool SPLIT>
+template <int D, bool OUT_K, bool OUT_V, int ENT, bool SPLIT, int BIAS = 0>
 __global__ void __launch_bounds__(64 * NW) flash_kernel(FlashParams P) {
   using G = RowGeo<D>;
   constexpr int ROW_BYTES = G::ROW_BYTES;
@@ -42,7 +42,8 @@ __global__ void __launch_bounds__(64 * NW) flash_kernel(FlashParams P) {
   constexpr int CH = G::CH;                   // 16-byte chunks per row
   constexpr int RPI = G::RPI;                 // rows filled by one 64-lane global -> LDS load
   auto swz = [](int row) { return G::swz(row); };
-  extern __shared__ __attribute__((aligned(16))) char smem[];  // [K|V][NSLOT][64 rows][2 D bytes]
+  extern __shared__ __attribute__((aligned(16))) char smem[];  // [K|V][NSLOT][64 rows][2 D bytes] [key biases]
+  static_assert(BIAS == 0 || (!SPLIT && ENT == 0), "the biased modes are whole-range passes without entropy");
 
   // XCD-aware placement: hardware deals workgroups to the 8 XCDs round-robin, so give each
   // XCD one contiguous range of work items; the query blocks of one (head, frame) then share
@@ -69,9 +70,13 @@ __global__ void __launch_bounds__(64 * NW) flash_kernel(FlashParams P) {
   const int nkeys = kend - kbeg;
   const int ntiles = (nkeys + BK - 1) / BK;
 
-  const long long qrow0 = (long long)prob * P.q_rows_per_problem;
-  const bf16_t* kbase = P.k + ((long long)prob * P.k_rows_per_problem + kbeg) * D;
-  const bf16_t* vbase = OUT_V ? P.v + ((long long)prob * P.k_rows_per_problem + kbeg) * D : nullptr;
+  const long long rs = P.row_stride ? P.row_stride : 1;  // distance between consecutive rows of a problem
+  const int inner = P.inner ? P.inner : 1;
+  const int p_out = prob / inner, p_in = prob - p_out * inner;
+  const long long qrow0 = (long long)p_out * P.q_rows_per_problem + (long long)p_in * P.inner_rows;
+  const long long krow0 = (long long)p_out * P.k_rows_per_problem + (long long)p_in * P.inner_rows;
+  const bf16_t* kbase = P.k + (krow0 + kbeg * rs) * D;
+  const bf16_t* vbase = OUT_V ? P.v + (krow0 + kbeg * rs) * D : nullptr;
 
   // ---- LDS addressing ----------------------------------------------------------------
   // staging: global -> LDS directly (global_load_lds_dwordx4).  One wave instruction fills 64
@@ -97,12 +102,12 @@ __global__ void __launch_bounds__(64 * NW) flash_kernel(FlashParams P) {
 #pragma unroll
     for (int r = 0; r < BK / (RPI * NW); ++r) {
       int key = min(t * BK + RPI * NW * r + st_key, nkeys - 1);
-      const bf16_t* src = kbase + (long long)key * D + st_lc * 8;
+      const bf16_t* src = kbase + (long long)key * rs * D + st_lc * 8;
       // wave-uniform LDS byte address in M0; lane lands at + 16 * lane
       const unsigned dst = __builtin_amdgcn_readfirstlane(kb + (RPI * NW * r + RPI * wave) * ROW_BYTES);
       asm volatile("s_mov_b32 m0, %1\n\ts_nop 0\n\tglobal_load_lds_dwordx4 %0, off" : : "v"(src), "s"(dst) : "memory", "m0");
       if (OUT_V) {
-        const bf16_t* vsrc = vbase + (long long)key * D + st_lc * 8;
+        const bf16_t* vsrc = vbase + (long long)key * rs * D + st_lc * 8;
         const unsigned vdst = dst + NSLOT * TILE_BYTES;
         asm volatile("s_mov_b32 m0, %1\n\ts_nop 0\n\tglobal_load_lds_dwordx4 %0, off" : : "v"(vsrc), "s"(vdst) : "memory", "m0");
       }
@@ -119,6 +124,13 @@ __global__ void __launch_bounds__(64 * NW) flash_kernel(FlashParams P) {
 #pragma unroll
     for (int r = 0; r < TILE_BYTES / (16 * 64 * NW); ++r) *reinterpret_cast<uint4*>(x3 + (r * 64 * NW + tid) * 16) = z;
     static_assert(TILE_BYTES % (16 * 64 * NW) == 0, "the clear covers the slot exactly");
+  }
+  // Biased modes: the additive term of every key of the problem, gathered once into LDS behind the tile slots
+  // (the launcher sizes the allocation: (ntiles + 1) * 64 floats; keys past the end get 0 and are masked anyway).
+  float* kb_lds = reinterpret_cast<float*>(smem + 2 * NSLOT * TILE_BYTES);
+  if (BIAS != 0) {
+    for (int l = tid; l < (ntiles + 1) * BK; l += 64 * NW)
+      kb_lds[l] = l < nkeys ? P.kb_scale * P.kbias[krow0 + (long long)(kbeg + l) * rs] : 0.f;
   }
 
   // ---- queries: B operand of S^T = K Q^T, kept in registers -------------------------
@@ -140,10 +152,10 @@ __global__ void __launch_bounds__(64 * NW) flash_kernel(FlashParams P) {
       qvalid[qt] = qvalid[qt] && inside;
       grow[qt] = inside ? gi : 0;
     }
-    const bf16_t* qp = P.q + (qrow0 + grow[qt]) * D + 8 * g;
+    const bf16_t* qp = P.q + (qrow0 + grow[qt] * rs) * D + 8 * g;
 #pragma unroll
     for (int ks = 0; ks < KS; ++ks) qreg[qt][ks] = *reinterpret_cast<const bf16x8*>(qp + 16 * ks);
-    float c = P.cR ? P.cR[qrow0 + grow[qt]] : 1.0f;
+    float c = P.cR ? P.cR[qrow0 + grow[qt] * rs] : 1.0f;
     c = fmaxf(c, P.cr_min);
     sc[qt] = P.row_scale * LOG2E / c;
   }
@@ -184,7 +196,28 @@ __global__ void __launch_bounds__(64 * NW) flash_kernel(FlashParams P) {
     msc[qt] = NEG_BIG;
     ltil[qt] = 0.f;
     hsum[qt] = 0.f;
+    // BIAS == 2: the reference of a row is given and never moves (every exponent is <= 0 by construction)
+    if (BIAS == 2) msc[qt] = P.qb_scale * P.qbias[qrow0 + grow[qt] * rs];
   }
+  float inv_sc[QT];
+#pragma unroll
+  for (int qt = 0; qt < QT; ++qt) inv_sc[qt] = BIAS != 0 ? 1.0f / sc[qt] : 0.f;
+  // Biased modes: logits of sub-tile `sub` (keys 32 sub .. 32 sub + 31) get their keys' terms, expressed in units of the
+  // raw product (divided by the row's scale) so that everything downstream treats them like any other logit.
+  auto add_key_bias = [&](f32x16 (&sacc)[QT], int sub) {
+    if (BIAS == 0) return;
+#pragma unroll
+    for (int c4 = 0; c4 < 4; ++c4) {
+      const float4 kb = *reinterpret_cast<const float4*>(kb_lds + 32 * sub + 8 * c4 + 4 * g);
+#pragma unroll
+      for (int qt = 0; qt < QT; ++qt) {
+        sacc[qt][4 * c4 + 0] = __builtin_fmaf(kb.x, inv_sc[qt], sacc[qt][4 * c4 + 0]);
+        sacc[qt][4 * c4 + 1] = __builtin_fmaf(kb.y, inv_sc[qt], sacc[qt][4 * c4 + 1]);
+        sacc[qt][4 * c4 + 2] = __builtin_fmaf(kb.z, inv_sc[qt], sacc[qt][4 * c4 + 2]);
+        sacc[qt][4 * c4 + 3] = __builtin_fmaf(kb.w, inv_sc[qt], sacc[qt][4 * c4 + 3]);
+      }
+    }
+  };
 
   // Software pipeline over 32-key sub-tiles n = 0, 1, ...  Step n carries two independent
   // instruction streams:
@@ -230,6 +263,12 @@ __global__ void __launch_bounds__(64 * NW) flash_kernel(FlashParams P) {
   float mpend[QT];     // references that take effect at the start of the next step
   bool moved = false;  // wave-uniform: some reference moves at the start of the next step
   auto look_ahead = [&](f32x16 (&snext)[QT]) {
+    if (BIAS == 2) {
+      moved = false;
+#pragma unroll
+      for (int qt = 0; qt < QT; ++qt) mpend[qt] = msc[qt];
+      return;
+    }
     bool grow = false;
     float cand[QT];
 #pragma unroll
@@ -242,7 +281,7 @@ __global__ void __launch_bounds__(64 * NW) flash_kernel(FlashParams P) {
     for (int qt = 0; qt < QT; ++qt) mpend[qt] = moved ? fmaxf(msc[qt], cand[qt]) : msc[qt];
   };
   auto step = [&](f32x16 (&scur)[QT], f32x16 (&snext)[QT], bf16x8 (&pbprev)[QT][2], bf16x8 (&pbcur)[QT][2],
-                  const char* next_ktile, int next_st, const char* prev_ktile, int prev_st, int keys_left) {
+                  const char* next_ktile, int next_st, const char* prev_ktile, int prev_st, int keys_left, int next_sub) {
     if (keys_left < 32) {
       // ragged end of the key range: rows keys_left .. 31 of this sub-tile are copies of the
       // last valid row; push their logits far down so that they get probability zero
@@ -267,6 +306,7 @@ __global__ void __launch_bounds__(64 * NW) flash_kernel(FlashParams P) {
     accumulate(prev_ktile, prev_st, pbprev);
 #pragma unroll
     for (int qt = 0; qt < QT; ++qt) subtile_probs<ENT>(scur[qt], sc[qt], msc[qt], ltil[qt], hsum[qt], pbcur[qt]);
+    add_key_bias(snext, next_sub);
     look_ahead(snext);
     // Keep this step's vector results in this step: without the pins below the compiler sinks
     // the probability code past the rescale branch to its first use, next to the MFMAs of the
@@ -304,6 +344,7 @@ __global__ void __launch_bounds__(64 * NW) flash_kernel(FlashParams P) {
     const bool active = qb * BQ + wave * (32 * QT) < P.nq;
     if (active) {
       logits(smem, 0, sA);
+      add_key_bias(sA, 0);
       look_ahead(sA);
     }
     const int last_left = nkeys - (ntiles - 1) * BK;  // 1..64 keys in the last tile
@@ -321,8 +362,8 @@ __global__ void __launch_bounds__(64 * NW) flash_kernel(FlashParams P) {
       const char* kn = smem + ((SLOT + 1) & 3) * TILE_BYTES;
       const int left0 = t == ntiles - 1 ? last_left : 64;
       if (active) {
-        step(sA, sB, pbB, pbA, kt, 1, kp, 1, left0);  // at t = 0: P^T = 0 against the cleared slot 3
-        step(sB, sA, pbA, pbB, kn, 0, kt, 0, left0 - 32);
+        step(sA, sB, pbB, pbA, kt, 1, kp, 1, left0, 2 * t + 1);  // at t = 0: P^T = 0 against the cleared slot 3
+        step(sB, sA, pbA, pbB, kn, 0, kt, 0, left0 - 32, 2 * t + 2);
       }
     };
     for (int t0 = 0; t0 < ntiles; t0 += 4) {
@@ -341,8 +382,9 @@ __global__ void __launch_bounds__(64 * NW) flash_kernel(FlashParams P) {
 #pragma unroll
   for (int qt = 0; qt < QT; ++qt) {
     const float lt = ltil[qt] + __shfl_xor(ltil[qt], 32);
-    const float inv = lt > 0.f ? 1.0f / lt : 0.f;
-    const long long row = qrow0 + grow[qt];
+    const float inv = BIAS == 2 ? 1.0f : (lt > 0.f ? 1.0f / lt : 0.f);  // BIAS == 2: the weights are final as they are
+    const long long row = qrow0 + grow[qt] * rs;
+    if (BIAS == 2 && qvalid[qt] && g == 0) P.cl[row] = lt;              // ... and their sum is an output
     if (!SPLIT) {
       if (P.lse != nullptr && qvalid[qt] && g == 0) P.lse[row] = LN2 * (msc[qt] + __log2f(lt));
       if (ENT == 1) {
@@ -404,6 +446,7 @@ __global__ void __launch_bounds__(64 * NW) flash_kernel(FlashParams P) {
     __builtin_amdgcn_wave_barrier();
     bf16_t* dst = OUT_K ? P.outk : P.outv;
     const int row_first = qb * BQ + wave * (32 * QT);
+    if (dst != nullptr)  // a pass that only wants the row statistics gives no destination
 #pragma unroll
     for (int ps = 0; ps < 32 * QT / RPI; ++ps) {
       const int lr = ps * RPI + lane / CH;  // row within the wave's block
@@ -417,7 +460,7 @@ __global__ void __launch_bounds__(64 * NW) flash_kernel(FlashParams P) {
       }
       if (ovalid) {
         uint4 w = *reinterpret_cast<const uint4*>(stage + lr * ROW_BYTES + pc * 16);
-        uint4* gp = reinterpret_cast<uint4*>(dst + (qrow0 + orow) * D + lc * 8);
+        uint4* gp = reinterpret_cast<uint4*>(dst + (qrow0 + orow * rs) * D + lc * 8);
         if (P.blend) w = average_bf16x8(w, *gp);
         *gp = w;
       }
@@ -462,17 +505,25 @@ __global__ void __launch_bounds__(128) merge_splits_kernel(const float* __restri
   if (lse != nullptr && c == 0) lse[prob * out_rows_per_problem + row] = LN2 * (mx + log2f(wsum));
 }
 
-template <int D, bool OUT_K, bool OUT_V, int ENT, bool SPLIT>
+constexpr int kMaxBiasedKeys = 8192 - BK;  // biased modes keep one float per key (+ one tile of padding) behind the tile slots: 32 KB
+
+template <int D, bool OUT_K, bool OUT_V, int ENT, bool SPLIT, int BIAS = 0>
 hipError_t launch_flash(const FlashParams& P, hipStream_t st) {
-  constexpr int LDS_BYTES = 2 * NSLOT * BK * D * 2;  // four K slots + four V slots: 128 KB at d = 128
-  auto kern = flash_kernel<D, OUT_K, OUT_V, ENT, SPLIT>;
+  constexpr int TILE_LDS = 2 * NSLOT * BK * D * 2;  // four K slots + four V slots: 128 KB at d = 128
+  constexpr int MAX_LDS = TILE_LDS + (BIAS != 0 ? (kMaxBiasedKeys + BK) * 4 : 0);
+  auto kern = flash_kernel<D, OUT_K, OUT_V, ENT, SPLIT, BIAS>;
   static bool configured = false;  // the attribute is per function, set once per process
   if (!configured) {
-    hipError_t e = hipFuncSetAttribute((const void*)kern, hipFuncAttributeMaxDynamicSharedMemorySize, LDS_BYTES);
+    hipError_t e = hipFuncSetAttribute((const void*)kern, hipFuncAttributeMaxDynamicSharedMemorySize, MAX_LDS);
     if (e != hipSuccess) return e;
     configured = true;
   }
-  hipLaunchKernelGGL(kern, dim3(P.blocks_per_xcd * 8), dim3(64 * NW), LDS_BYTES, st, P);
+  int lds = TILE_LDS;
+  if (BIAS != 0) {
+    if (P.nk > kMaxBiasedKeys || P.nsplit != 1 || P.kbias == nullptr) return hipErrorInvalidValue;
+    lds += ((P.nk + BK - 1) / BK + 1) * BK * 4;
+  }
+  hipLaunchKernelGGL(kern, dim3(P.blocks_per_xcd * 8), dim3(64 * NW), lds, st, P);
   return hipGetLastError();
 }
 
@@ -594,6 +645,49 @@ hipError_t launch_first_frame_flash(const bf16_t* q, const bf16_t* k, const bf16
   hipLaunchKernelGGL(merge_splits_kernel, dim3((unsigned)((long long)dm.BH * nrows)), dim3(dm.d), 0, st, P.part_o,
                      P.part_lse, out, lse, ns, (long long)dm.BH * nrows, nrows, dm.N, row_list, (int)dm.N);
   return hipGetLastError();
+}
+
+// The temporal factor through the blocked-softmax kernel, for any number of frames T (Eq. L with Eq. alpha_R / c_R, and
+// the apply-to-V of App. A).  A problem is one (head, position i); its rows are the T frames of that position, b rows
+// apart in the frame-major tensors.  With u[j,k] = q_scale (Q[j] . alpha_L[k]) - c_L[k]:
+//   last sweep     one pass, queries Q[j], keys alpha_L[k] with the additive term -c_L[k], values y[k]:
+//                  out[j] = sum_k softmax_k(u[j,:])[k] y[k];
+//   fitting sweep  pass 1, the same queries and keys without a product: lse[j] = log sum_k exp u[j,k];
+//                  pass 2 with the roles exchanged, queries alpha_L[k] (fixed reference c_L[k]), keys Q[j] with the
+//                  additive term -lse[j], values Q[j]: the weights exp(u[j,k] - lse[j]) = L[j,k] are final, so
+//                  alpha_R[k] = sum_j L[j,k] Q[j] and c_R[k] = sum_j L[j,k] are plain unnormalised sums.
+// lse_scratch: BH * N floats (fitting sweep only).
+bool temporal_flash_supported(const Dims& dm) { return (dm.d == 128 || dm.d == 64) && dm.T <= kMaxBiasedKeys; }
+
+hipError_t launch_l_update_flash(const bf16_t* q, const bf16_t* aL, const float* cL, const bf16_t* y, bf16_t* aR, float* cR,
+                                 bf16_t* out, float* lse_scratch, const Dims& dm, float q_scale, hipStream_t st) {
+  if (!temporal_flash_supported(dm)) return hipErrorInvalidValue;
+  FlashParams P = {};
+  P.q_rows_per_problem = dm.N; P.k_rows_per_problem = dm.N;
+  P.inner = dm.b; P.inner_rows = 1; P.row_stride = dm.b;
+  P.nq = dm.T; P.nk = dm.T;
+  P.nqb = (dm.T + BQ - 1) / BQ;
+  P.nsplit = 1;
+  P.keys_per_split = ((dm.T + BK - 1) / BK) * BK;
+  const long long total = (long long)dm.BH * dm.b * P.nqb;
+  if (total > 0x3fffffffLL) return hipErrorInvalidValue;
+  P.total_blocks = (int)total;
+  P.blocks_per_xcd = (P.total_blocks + 7) / 8;
+  P.row_scale = q_scale; P.cr_min = 0.f;
+  P.kb_scale = -LOG2E;
+  const bool d128 = dm.d == 128;
+  if (y != nullptr) {
+    P.q = q; P.k = aL; P.v = y; P.outv = out; P.kbias = cL;
+    return d128 ? launch_flash<128, false, true, 0, false, 1>(P, st) : launch_flash<64, false, true, 0, false, 1>(P, st);
+  }
+  if (lse_scratch == nullptr) return hipErrorInvalidValue;
+  P.q = q; P.k = aL; P.outk = nullptr; P.lse = lse_scratch; P.kbias = cL;
+  hipError_t e = d128 ? launch_flash<128, true, false, 0, false, 1>(P, st) : launch_flash<64, true, false, 0, false, 1>(P, st);
+  if (e != hipSuccess) return e;
+  P.q = aL; P.k = q; P.outk = aR; P.cl = cR; P.lse = nullptr;
+  P.kbias = lse_scratch;          // natural log, like c_L: the same scale -log2(e) applies
+  P.qbias = cL; P.qb_scale = LOG2E;
+  return d128 ? launch_flash<128, true, false, 0, false, 2>(P, st) : launch_flash<64, true, false, 0, false, 2>(P, st);
 }
 
 // Attention-sink averaging (Sec. 4.4): all N queries of a head against its first frame's b keys,

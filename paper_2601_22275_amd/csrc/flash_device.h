@@ -45,7 +45,21 @@ struct FlashParams {
   float row_scale;
   float cr_min;
   int blend;            // outv <- (outv + result) / 2 instead of outv <- result
-  const int* q_index;   // flash_kernel: query row r of a problem is row q_index[r] of it (null: row r); entries
+  // flash_kernel only.  Rows of a problem need not be adjacent: row r of problem p is row
+  //   (p / inner) * rows_per_problem + (p % inner) * inner_rows + r * row_stride     (inner = 0 means 1)
+  // of its tensor, the same rule for queries and keys.  The temporal factor walks frame-major tensors this
+  // way: problem = (head, position), rows = frames, row_stride = b.  row_stride = 0 means 1.
+  int inner;
+  long long inner_rows;
+  long long row_stride;
+  // Biased modes (template parameter BIAS != 0): logit of (query r, key l) = sc (q . k) + kb_scale * kbias[key row l]
+  // (kbias indexed like the key rows); BIAS == 2 additionally fixes the reference of query r at
+  // qb_scale * qbias[query row r], keeps the sums unnormalised and stores the sum of the weights in `cl`.
+  const float* kbias;
+  const float* qbias;
+  float kb_scale;
+  float qb_scale;
+  const int* q_index;   // query row r of a problem is row q_index[r] of it (null: row r); entries
                         // outside [0, q_index_limit) are skipped
   int q_index_limit;
   int own_tile_first;   // flash2: queries and keys are the same rows (R-update): start the key loop at the query block's own tile

@@ -224,6 +224,104 @@ __global__ void __launch_bounds__(256) l_update_generic_kernel(const E* __restri
   }
 }
 
+// The temporal factor for any number of frames, without a T x T block in LDS: one wave per row of a position's
+// block, two passes over the other side's rows (statistics, then sums), the logits recomputed in the second.
+//   weight of row l:  w[l] = exp(scale * (x . A[l]) + add_scale * add[l] - ref)
+//   FIXED == false:   ref = the row's log-sum-exp (a softmax); out = sum_l w[l] V[l]; lse_out = ref
+//   FIXED == true:    ref is given, the weights are final as they are; out = sum_l w[l] V[l], sum_out = sum_l w[l]
+// A, add and V are rows of frame-major tensors `stride` rows apart (the position's frames).
+template <typename E, bool FIXED>
+__device__ void temporal_row(const E* __restrict__ x, float scale, const E* __restrict__ A, const float* __restrict__ add,
+                             float add_scale, const E* __restrict__ V, long long stride, int n, int d, float ref_fixed,
+                             E* __restrict__ out, float* __restrict__ lse_out, float* __restrict__ sum_out, float* sq,
+                             float* sp) {
+  const int lane = threadIdx.x;
+  for (int c = lane; c < d; c += 64) sq[c] = load_f<E>(x + c);
+  __syncthreads();
+  auto logit = [&](int l) {
+    const E* ar = A + (long long)l * stride * d;
+    float z = 0.f;
+    for (int c = 0; c < d; ++c) z += sq[c] * load_f<E>(ar + c);
+    return z * scale + add_scale * add[(long long)l * stride];
+  };
+  float ref = ref_fixed;
+  if (!FIXED) {
+    float m = -INFINITY, S = 0.f;  // online max / sum per lane, merged across the wave
+    for (int l = lane; l < n; l += 64) {
+      const float z = logit(l);
+      const float mn = fmaxf(m, z);
+      S = S * expf(m - mn) + expf(z - mn);  // exp(-inf) = 0 on the first key
+      m = mn;
+    }
+    for (int off = 32; off >= 1; off >>= 1) {
+      const float mo = __shfl_xor(m, off), So = __shfl_xor(S, off);
+      const float mn = fmaxf(m, mo);
+      S = (S > 0.f ? S * expf(m - mn) : 0.f) + (So > 0.f ? So * expf(mo - mn) : 0.f);
+      m = mn;
+    }
+    ref = m + logf(S);
+    if (lse_out != nullptr && lane == 0) *lse_out = ref;
+  }
+  if (out == nullptr) return;
+  float acc[kMaxD / 64];
+#pragma unroll
+  for (int u = 0; u < kMaxD / 64; ++u) acc[u] = 0.f;
+  float wsum = 0.f;
+  for (int l0 = 0; l0 < n; l0 += 64) {
+    const int l = l0 + lane;
+    const float w = l < n ? expf(logit(l) - ref) : 0.f;
+    wsum += w;
+    __syncthreads();
+    sp[lane] = w;
+    __syncthreads();
+    const int cnt = n - l0 < 64 ? n - l0 : 64;
+    for (int t = 0; t < cnt; ++t) {
+      const float wt = sp[t];
+      const E* vr = V + (long long)(l0 + t) * stride * d;
+#pragma unroll
+      for (int u = 0; u < kMaxD / 64; ++u) {
+        const int c = lane + 64 * u;
+        if (c < d) acc[u] += wt * load_f<E>(vr + c);
+      }
+    }
+  }
+#pragma unroll
+  for (int u = 0; u < kMaxD / 64; ++u) {
+    const int c = lane + 64 * u;
+    if (c < d) store_f<E>(out + c, acc[u]);
+  }
+  if (sum_out != nullptr) {
+    for (int off = 32; off >= 1; off >>= 1) wsum += __shfl_xor(wsum, off);
+    if (lane == 0) *sum_out = wsum;
+  }
+}
+
+// MODE 0: last sweep, out[j,i] = sum_k L[j,k] y[k,i]           (Eq. L and the apply-to-V of App. A)
+// MODE 1: fitting sweep, first pass: lse[j,i] = log sum_k exp(q_scale Q[j,i] . aL[k,i] - cL[k,i])
+// MODE 2: fitting sweep, second pass: aR[k,i] = sum_j L[j,k] Q[j,i], cR[k,i] = sum_j L[j,k]   (Eq. alpha_R / c_R),
+//         L[j,k] = exp(q_scale Q[j,i] . aL[k,i] - cL[k,i] - lse[j,i])
+template <typename E, int MODE>
+__global__ void __launch_bounds__(64) l_update_rows_kernel(const E* __restrict__ q, const E* __restrict__ aL,
+                                                           const float* __restrict__ cL, const E* __restrict__ y,
+                                                           E* __restrict__ aR, float* __restrict__ cR,
+                                                           E* __restrict__ out, float* __restrict__ lse, int T, int b,
+                                                           int d, float q_scale) {
+  __shared__ float sq[kMaxD];
+  __shared__ float sp[64];
+  const int i = blockIdx.x, f = blockIdx.y;  // position, frame of the row this wave owns
+  const long long col = (long long)blockIdx.z * T * b + i;  // frame 0 of this position
+  const long long row = col + (long long)f * b;
+  if (MODE == 0)
+    temporal_row<E, false>(q + row * d, q_scale, aL + col * d, cL + col, -1.f, y + col * d, b, T, d, 0.f, out + row * d,
+                           nullptr, nullptr, sq, sp);
+  else if (MODE == 1)
+    temporal_row<E, false>(q + row * d, q_scale, aL + col * d, cL + col, -1.f, nullptr, b, T, d, 0.f, nullptr, lse + row,
+                           nullptr, sq, sp);
+  else
+    temporal_row<E, true>(aL + row * d, q_scale, q + col * d, lse + col, -1.f, q + col * d, b, T, d, cL[row], aR + row * d,
+                          nullptr, cR + row, sq, sp);
+}
+
 // Token-row permutation copy, 4-byte words.
 __global__ void __launch_bounds__(256) permute_tokens_kernel(const uint32_t* __restrict__ in, uint32_t* __restrict__ out,
                                                              int T, int b, int row_words, int to_pos_major) {
@@ -297,9 +395,30 @@ hipError_t launch_r_update_generic(const E* aR, const float* cR, const E* k, con
   return hipGetLastError();
 }
 
+constexpr int kBlockInLdsMaxT = 200;  // l_update_generic_kernel keeps T * T floats in LDS
+
+bool l_update_generic_needs_lse(const Dims& dm) { return dm.T > kBlockInLdsMaxT; }
+
 template <typename E>
 hipError_t launch_l_update_generic(const E* q, const E* aL, const float* cL, const E* y, E* aR, float* cR, E* out,
-                                   const Dims& dm, float q_scale, hipStream_t st) {
+                                   float* lse_scratch, const Dims& dm, float q_scale, hipStream_t st) {
+  if (dm.T > kBlockInLdsMaxT) {
+    // more frames than the block-in-LDS kernel holds: one wave per row, logits recomputed
+    dim3 grid(dm.b, dm.T, dm.BH);
+    if (y != nullptr) {
+      hipLaunchKernelGGL((l_update_rows_kernel<E, 0>), grid, dim3(64), 0, st, q, aL, cL, y, aR, cR, out, lse_scratch, dm.T,
+                         dm.b, dm.d, q_scale);
+      return hipGetLastError();
+    }
+    if (lse_scratch == nullptr) return hipErrorInvalidValue;
+    hipLaunchKernelGGL((l_update_rows_kernel<E, 1>), grid, dim3(64), 0, st, q, aL, cL, y, aR, cR, out, lse_scratch, dm.T,
+                       dm.b, dm.d, q_scale);
+    hipError_t e = hipGetLastError();
+    if (e != hipSuccess) return e;
+    hipLaunchKernelGGL((l_update_rows_kernel<E, 2>), grid, dim3(64), 0, st, q, aL, cL, y, aR, cR, out, lse_scratch, dm.T,
+                       dm.b, dm.d, q_scale);
+    return hipGetLastError();
+  }
   dim3 grid(dm.b, dm.BH);
   size_t lds = (size_t)dm.T * dm.T * sizeof(float);
   hipError_t e;
@@ -365,9 +484,9 @@ template hipError_t launch_r_update_generic<float>(const float*, const float*, c
 template hipError_t launch_r_update_generic<bf16_t>(const bf16_t*, const float*, const bf16_t*, const bf16_t*, bf16_t*,
                                                     float*, bf16_t*, float*, const Dims&, float, float, hipStream_t);
 template hipError_t launch_l_update_generic<float>(const float*, const float*, const float*, const float*, float*,
-                                                   float*, float*, const Dims&, float, hipStream_t);
+                                                   float*, float*, float*, const Dims&, float, hipStream_t);
 template hipError_t launch_l_update_generic<bf16_t>(const bf16_t*, const bf16_t*, const float*, const bf16_t*, bf16_t*,
-                                                    float*, bf16_t*, const Dims&, float, hipStream_t);
+                                                    float*, bf16_t*, float*, const Dims&, float, hipStream_t);
 template hipError_t launch_first_frame_generic<float>(const float*, const float*, const float*, float*, float*,
                                                       const Dims&, int, const int*, hipStream_t);
 template hipError_t launch_first_frame_generic<bf16_t>(const bf16_t*, const bf16_t*, const bf16_t*, bf16_t*, float*,

@@ -259,7 +259,12 @@ L_CASES = [
     (4, 4, 4, 32, "f32"), (7, 1, 5, 20, "f32"), (5, 2, 3, 96, "bf16"),
     (5, 2, 3, 64, "bf16"), (21, 1, 7, 64, "bf16"), (32, 1, 5, 64, "bf16"), (81, 1, 5, 64, "bf16"), (128, 1, 2, 64, "bf16"),
     (1, 2, 3, 128, "bf16"), (21, 1, 7, 128, "bf16"), (33, 1, 3, 128, "bf16"),
-    (81, 1, 5, 128, "bf16"), (128, 1, 2, 128, "bf16"), (130, 1, 2, 128, "bf16"),
+    (81, 1, 5, 128, "bf16"), (128, 1, 2, 128, "bf16"),
+    # more than 128 frames: the temporal factor runs through the blocked-softmax kernel (strided rows, additive key terms)
+    (129, 1, 3, 128, "bf16"), (130, 1, 2, 128, "bf16"), (200, 1, 3, 64, "bf16"), (256, 1, 2, 128, "bf16"),
+    (257, 1, 3, 64, "bf16"), (300, 2, 2, 128, "bf16"), (513, 1, 2, 128, "bf16"), (520, 1, 3, 64, "bf16"),
+    # plain-ALU kernels beyond the 200 frames whose T x T block fits LDS: one wave per row, logits recomputed
+    (200, 1, 2, 16, "f32"), (201, 1, 3, 24, "f32"), (333, 2, 1, 96, "bf16"), (700, 1, 1, 8, "f32"),
 ]
 
 
@@ -469,6 +474,11 @@ E2E = [
     (81, 3, 5, 128, "bf16", 2, True),         # T = 81: three waves per position
     (1, 9, 11, 128, "bf16", 2, False),        # single frame: exact attention
     (40, 1, 1, 128, "bf16", 2, False),        # single position: exact attention over frames
+    (260, 3, 5, 128, "bf16", 2, True),        # more frames than positions: temporal factor on the blocked-softmax kernel
+    (512, 1, 8, 64, "bf16", 2, False),        # m = 512 blocks of b = 8
+    (300, 1, 1, 64, "bf16", 3, False),        # single position, 300 frames: exact attention over frames
+    (230, 2, 3, 16, "f32", 2, True),          # plain-ALU kernels with more than 200 frames
+    (260, 1, 4, 96, "bf16", 2, False),
 ]
 
 
