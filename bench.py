@@ -153,6 +153,52 @@ def sweep_frames(args) -> int:
     return 0
 
 
+def sweep_budget(args) -> int:
+    """The paper's computation-budget study (App. "Various Monarch Computation Budgets"): N = 2^15 tokens as m blocks of
+    b tokens for every power-of-two split from (8, 4096) to (512, 64), 12 heads, d = 64, 2 sweeps.  One JSON line per
+    split: ms per call, the method's FLOPs for that split and the phase times."""
+    import torch
+
+    from paper_2601_22275_amd import binding, synth
+
+    dev = torch.device("cuda:0")
+    binding.lib()
+    for m, b in synth.BUDGET_SPLITS:
+        wl = synth.WORKLOADS[f"budget-{m}x{b}"]
+        q, k, v = synth.make_inputs(wl)
+        tq, tk, tv = (torch.from_numpy(x).to(dev).view(torch.bfloat16).view(1, wl.heads, wl.N, wl.d) for x in (q, k, v))
+        out = torch.empty_like(tq)
+        ws = torch.empty(binding.workspace_bytes(1, wl.heads, wl.T, wl.Hs, wl.Ws, wl.d, wl.iters, wl.recompute, 2),
+                         dtype=torch.uint8, device=dev)
+        binding.set_workspace(ws)
+
+        def step():
+            binding.attention(tq, tk, tv, wl.T, wl.Hs, wl.Ws, wl.iters, wl.recompute, out=out)
+
+        for _ in range(args.warmup):
+            step()
+        torch.cuda.synchronize()
+        e0, e1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+        e0.record()
+        for _ in range(args.steps):
+            step()
+        e1.record()
+        torch.cuda.synchronize()
+        ms = e0.elapsed_time(e1) / args.steps
+        binding.set_phase_timing(True)
+        acc = {}
+        for _ in range(args.steps):
+            step()
+            for name, t in binding.get_phase_timing():
+                acc.setdefault(name, []).append(t)
+        binding.set_phase_timing(False)
+        binding.set_workspace(None)
+        fl = synth.algorithmic_flops(1, wl.heads, wl.T, wl.b, wl.d, wl.iters, wl.recompute)
+        print(json.dumps({"m": m, "b": b, "N": wl.N, "ms": ms, "gflop_per_call": fl / 1e9, "tflops": fl / ms / 1e9,
+                          "phase_ms": {n: sum(x) / len(x) for n, x in acc.items()}}), flush=True)
+    return 0
+
+
 def bench_backward(args) -> int:
     """Backward of one blocked-softmax pass with entropy (Alg. 2) on the workload's per-frame problems:
     dq, dk, dv for every (head, frame) from K, V, the forward outputs and seeded random dO, dH.  One JSON
@@ -217,6 +263,8 @@ def main() -> int:
                     help="time the Alg. 2 backward of the workload's per-frame softmax blocks instead of the forward path")
     ap.add_argument("--graph", action="store_true",
                     help="capture one call in a HIP graph and time replays (for launch-bound small workloads)")
+    ap.add_argument("--sweep-budget", action="store_true",
+                    help="time the (m, b) splits of N = 2^15 tokens from (8, 4096) to (512, 64) instead of the benchmark")
     ap.add_argument("--sweep-frames", action="store_true",
                     help="time T = 20..48 frames of 28x52 tokens against exact dense attention instead of the benchmark")
     args = ap.parse_args()
@@ -234,6 +282,8 @@ def main() -> int:
         return 2
     if args.sweep_frames:
         return sweep_frames(args)
+    if args.sweep_budget:
+        return sweep_budget(args)
     if args.backward:
         return bench_backward(args)
     binding.lib()  # fail loudly when the HIP library is missing

@@ -70,6 +70,16 @@ for _lg in range(10, 17):
     WORKLOADS[_n] = Workload(_n, 10 + _lg, 1, 12, 32, 1, (1 << _lg) // 32, 64, "bf16", 2, False)
 
 
+# The paper's study of computation budgets (App. "Various Monarch Computation Budgets"): one sequence of
+# N = 2^15 tokens factored as m blocks of b tokens for every power-of-two split from (8, 4096) to (512, 64);
+# the arithmetic is smallest near m = b = sqrt(N), the traffic falls as b grows.  d = 64, 12 heads, 2 sweeps as
+# in the kernel benchmark above (the appendix gives figures only, no numbers).
+BUDGET_SPLITS = [(8, 4096), (16, 2048), (32, 1024), (64, 512), (128, 256), (256, 128), (512, 64)]
+for _m, _b in BUDGET_SPLITS:
+    _n = f"budget-{_m}x{_b}"
+    WORKLOADS[_n] = Workload(_n, 30 + _m.bit_length(), 1, 12, _m, 1, _b, 64, "bf16", 2, False)
+
+
 def f32_to_bf16_bits(x: np.ndarray) -> np.ndarray:
     """Round-to-nearest-even float32 -> bf16 bit patterns (uint16)."""
     u = np.ascontiguousarray(x, dtype=np.float32).view(np.uint32)

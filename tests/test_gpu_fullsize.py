@@ -4,6 +4,7 @@ The oracle follows a subset of query positions exactly (each position's iteratio
 only on its own T queries and on all of K, V), so full-size runs are checked on sampled
 positions over all frames, plus properties that need no oracle.
 """
+import dataclasses
 import math
 
 import numpy as np
@@ -25,9 +26,11 @@ def env():
     return torch, binding, torch.device("cuda:0")
 
 
-def _run_workload(env, name, heads, n_pos, seed):
+def _run_workload(env, name, heads, n_pos, seed, iters=None, wl=None):
     torch, binding, dev = env
-    wl = synth.WORKLOADS[name]
+    wl = synth.WORKLOADS[name] if wl is None else wl
+    if iters is not None:
+        wl = dataclasses.replace(wl, iters=iters)
     q, k, v = synth.make_inputs(wl, heads=heads)
     tq, tk, tv = (torch.from_numpy(x).to(dev).view(torch.bfloat16).view(1, len(heads), wl.N, wl.d) for x in (q, k, v))
     out = binding.attention(tq, tk, tv, wl.T, wl.Hs, wl.Ws, wl.iters, wl.recompute)
@@ -61,6 +64,27 @@ def test_wan_480p_clip_sampled_positions(env):
 def test_wan_720p_clip_sampled_positions(env):
     """b = 3600 (15 query blocks, ragged), T = 21 padded to 32 in the temporal pass; 2 of the 40 heads."""
     _run_workload(env, "wan14b-720p", [0, 39], 16, 3)
+
+
+@pytest.mark.parametrize("iters", [1, 3])
+def test_wan_720p_clip_one_and_three_sweeps(env, iters):
+    """The 720p workload with 1 and 3 sweeps (the pair that separates the cost of one sweep in the benchmark)."""
+    _run_workload(env, "wan14b-720p", [17], 16, 30 + iters, iters=iters)
+
+
+@pytest.mark.parametrize("m,b", synth.BUDGET_SPLITS)
+def test_computation_budget_splits_of_32k_tokens(env, m, b):
+    """N = 2^15 tokens as m blocks of b, every power-of-two split from (8, 4096) to (512, 64), d = 64: from four
+    query blocks per R-update problem and one wave per temporal block to one tile per R-update problem and the
+    temporal factor on the blocked-softmax kernel (m = 256, 512)."""
+    _run_workload(env, f"budget-{m}x{b}", [0, 11], 20, 40 + m.bit_length())
+
+
+def test_blocks_of_two_frames(env):
+    """Block size b = 2 H W (two frames per spatial block, half as many temporal blocks), the paper's block-size
+    ablation: the same call with T / 2 frames of 2 H x W tokens.  20 frames of 28 x 52 tokens -> m = 10, b = 2912."""
+    wl = synth.Workload("two-frame-blocks-20x28x52", 7, 1, 12, 10, 56, 52, 128, "bf16", 2, True)
+    _run_workload(env, wl.name, [0, 7], 24, 9, wl=wl)
 
 
 def test_million_token_stress_single_head(env):
