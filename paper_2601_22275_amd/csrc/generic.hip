@@ -322,24 +322,41 @@ __global__ void __launch_bounds__(64) l_update_rows_kernel(const E* __restrict__
                           nullptr, cR + row, sq, sp);
 }
 
-// Token-row permutation copy, 4-byte words.
-__global__ void __launch_bounds__(256) permute_tokens_kernel(const uint32_t* __restrict__ in, uint32_t* __restrict__ out,
-                                                             int T, int b, int row_words, int to_pos_major) {
-  const long long N = (long long)T * b;
-  const long long head0 = (long long)blockIdx.y * N;
-  const long long total = N * row_words;
-  for (long long e = (long long)blockIdx.x * 256 + threadIdx.x; e < total; e += (long long)gridDim.x * 256) {
-    long long p = e / row_words;   // destination row
-    int w = (int)(e % row_words);
-    long long src;
-    if (to_pos_major) {            // out[i*T + j] = in[j*b + i]
-      long long i = p / T, j = p % T;
-      src = j * b + i;
-    } else {                       // out[j*b + i] = in[i*T + j]
-      long long j = p / b, i = p % b;
-      src = i * T + j;
+// Token-row permutation copy (the stride permutation P of Sec. 3.1 applied to the rows of a [T*b, row] tensor and
+// its inverse).  Element = one W-byte word of a destination row; every thread moves UNR of them, all loads issued
+// before the first store.  IDX is the integer type of the flat word index (32-bit whenever it fits: the two
+// divisions per word are what the copy costs beside its memory traffic).
+template <typename W, typename IDX, int UNR>
+__global__ void __launch_bounds__(256) permute_tokens_kernel(const W* __restrict__ in, W* __restrict__ out, int T, int b,
+                                                             int row_words, int to_pos_major) {
+  const IDX N = (IDX)T * (IDX)b;
+  const long long head0 = (long long)blockIdx.y * (long long)N * row_words;
+  const IDX total = N * (IDX)row_words;
+  const IDX stride = (IDX)gridDim.x * 256;
+  for (IDX e0 = (IDX)blockIdx.x * 256 + threadIdx.x; e0 < total; e0 += stride * UNR) {
+    W val[UNR];
+#pragma unroll
+    for (int u = 0; u < UNR; ++u) {
+      const IDX e = e0 + (IDX)u * stride;
+      if (e < total) {
+        const IDX p = e / (IDX)row_words;   // destination row
+        const IDX w = e - p * (IDX)row_words;
+        IDX src;
+        if (to_pos_major) {                 // out[i*T + j] = in[j*b + i]
+          const IDX i = p / (IDX)T, j = p - i * (IDX)T;
+          src = j * (IDX)b + i;
+        } else {                            // out[j*b + i] = in[i*T + j]
+          const IDX j = p / (IDX)b, i = p - j * (IDX)b;
+          src = i * (IDX)T + j;
+        }
+        val[u] = in[head0 + (long long)src * row_words + w];
+      }
     }
-    out[(head0 + p) * row_words + w] = in[(head0 + src) * row_words + w];
+#pragma unroll
+    for (int u = 0; u < UNR; ++u) {
+      const IDX e = e0 + (IDX)u * stride;
+      if (e < total) out[head0 + (long long)e] = val[u];
+    }
   }
 }
 
@@ -468,15 +485,30 @@ hipError_t launch_fill_head_prefix(float* p, float value, long long count, long 
   return hipGetLastError();
 }
 
+template <typename W>
+hipError_t launch_permute_words(const void* in, void* out, const Dims& dm, int row_words, int to_pos_major,
+                                hipStream_t st) {
+  constexpr int UNR = 4;
+  const long long total = dm.N * row_words;
+  long long blocks = (total + 256 * UNR - 1) / (256 * UNR);
+  if (blocks > 16384) blocks = 16384;
+  dim3 grid((unsigned)blocks, dm.BH);
+  // the flat index runs up to total + UNR * grid * 256 before its bound is tested
+  if (total + (long long)UNR * 16384 * 256 < 0x7fffffffLL)
+    hipLaunchKernelGGL((permute_tokens_kernel<W, unsigned, UNR>), grid, dim3(256), 0, st, (const W*)in, (W*)out, dm.T,
+                       dm.b, row_words, to_pos_major);
+  else
+    hipLaunchKernelGGL((permute_tokens_kernel<W, long long, UNR>), grid, dim3(256), 0, st, (const W*)in, (W*)out, dm.T,
+                       dm.b, row_words, to_pos_major);
+  return hipGetLastError();
+}
+
+// in and out are rows of row_bytes (a multiple of 4); 16-byte words when the rows and both pointers allow it
 hipError_t launch_permute_tokens(const void* in, void* out, const Dims& dm, int row_bytes, int to_pos_major,
                                  hipStream_t st) {
-  long long total = dm.N * (row_bytes / 4);
-  long long blocks = (total + 255) / 256;
-  if (blocks > 4096) blocks = 4096;
-  dim3 grid((unsigned)blocks, dm.BH);
-  hipLaunchKernelGGL(permute_tokens_kernel, grid, dim3(256), 0, st, (const uint32_t*)in, (uint32_t*)out, dm.T, dm.b,
-                     row_bytes / 4, to_pos_major);
-  return hipGetLastError();
+  const bool wide = row_bytes % 16 == 0 && ((uintptr_t)in | (uintptr_t)out) % 16 == 0;
+  if (wide) return launch_permute_words<uint4>(in, out, dm, row_bytes / 16, to_pos_major, st);
+  return launch_permute_words<uint32_t>(in, out, dm, row_bytes / 4, to_pos_major, st);
 }
 
 template hipError_t launch_r_update_generic<float>(const float*, const float*, const float*, const float*, float*,

@@ -87,6 +87,21 @@ def test_blocks_of_two_frames(env):
     _run_workload(env, wl.name, [0, 7], 24, 9, wl=wl)
 
 
+def test_permutation_copy_at_headline_shape(env):
+    """The stride permutation of 12 x 117,936 rows of 256 bytes (the benchmark's copy calibration) and of rows of
+    12 bytes (the 4-byte-word form), bit-exact against the oracle's index map, and back."""
+    torch, binding, dev = env
+    wl = synth.WORKLOADS["long-81x28x52"]
+    perm, _ = O.index_maps(wl.T, wl.b)
+    tperm = torch.from_numpy(perm.astype(np.int64)).to(dev)
+    for d, dt in ((128, torch.int16), (3, torch.int32)):
+        g = torch.Generator(device=dev).manual_seed(d)
+        x = torch.randint(-30000, 30000, (1, 3, wl.N, d), device=dev, generator=g, dtype=torch.int32).to(dt)
+        got = binding.permute_tokens(x, wl.T, wl.Hs, wl.Ws, True)
+        assert torch.equal(got, x[:, :, tperm, :])
+        assert torch.equal(binding.permute_tokens(got, wl.T, wl.Hs, wl.Ws, False), x)
+
+
 def test_million_token_stress_single_head(env):
     """N = 991,440 tokens: b = 12,240 keys per frame (192 key tiles, ragged), one sweep, no
     recomputation; one of the 12 heads (row offsets beyond 2^31 bytes within the head)."""
@@ -174,6 +189,20 @@ def test_backward_at_headline_shape_sampled_frames(env):
             err = U.rel_l2(g[kf], r)
             print(f"backward frame {kf} {name}: rel {err:.2e}")
             assert err <= 1e-2
+        # and the whole chain: the oracle's own forward (fp64, from the definitions) feeding its backward
+        Oo, l64, H64 = O.entropy_attention(q64[kf], k64[kf], v64[kf], np.full(wl.b, s))
+        ref = O.entropy_attention_backward(q64[kf], k64[kf], v64[kf], Oo, do64[kf], l64, H64,
+                                           dH.reshape(wl.T, wl.b)[kf].astype(np.float64), np.full(wl.b, s))
+        # D = rowsum(dO o O) sees O rounded to bf16: first-order effect on dQ and dK (two standard deviations of the
+        # sum of d independent roundings per row) added to the 1e-2
+        dD = 2.0 * 2.0 ** -9 / math.sqrt(3.0) * np.sqrt(((do64[kf] * Oo) ** 2).sum(axis=1))
+        P = np.exp((q64[kf] @ k64[kf].T) * s - l64[:, None])
+        extra = (np.linalg.norm((s * dD)[:, None] * (P @ k64[kf])) / np.linalg.norm(ref[0]),
+                 np.linalg.norm((P * (s * dD)[:, None]).T @ np.abs(q64[kf])) / np.linalg.norm(ref[1]), 0.0)
+        for name, g, r, ex in zip(("dq", "dk", "dv"), got, ref, extra):
+            err = U.rel_l2(g[kf], r)
+            print(f"forward+backward frame {kf} {name}: rel {err:.2e} of {1e-2 + ex:.2e} allowed")
+            assert err <= 1e-2 + ex
 
 
 def test_headline_shape_ablation_variants_sampled_positions(env):
