@@ -254,9 +254,9 @@ def main() -> int:
                          "to separate the cost of a sweep)")
     ap.add_argument("--entropy", choices=["online", "identity"], default="online")
     ap.add_argument("--no-cpu-baseline", action="store_true")
-    ap.add_argument("--flash-variant", type=int, choices=[0, 1], default=None,
-                    help="bf16 MFMA R-update kernels: 0 two waves per SIMD (the library's default), 1 one wave per SIMD "
-                         "with two query tiles per wave")
+    ap.add_argument("--flash-variant", type=int, choices=[0, 1, 2], default=None,
+                    help="bf16 MFMA R-update kernels: 0 two waves per SIMD, 1 one wave per SIMD with two query tiles per "
+                         "wave, 2 the latter for the update with values only (default: the library's setting)")
     ap.add_argument("--copy-calibration", action="store_true",
                     help="also run one token-permutation copy of known size (reference for HBM byte counters)")
     ap.add_argument("--backward", action="store_true",
@@ -369,7 +369,7 @@ def main() -> int:
         # the logits, R K (alpha_L), c_L and R V (y) in one launch: three b x b x d products per frame.
         # (With the two-pass form the phase is two launches.)
         fl, t_ms = 6.0 * BH * T * b * b * d, phases["r_update_last"]
-        if bf16 and d in (64, 128) and variant == 1:
+        if bf16 and d in (64, 128) and variant in (1, 2):
             kern, what = "flash2_kernel", "flash2_kernel (last R-update: logits, R K, c_L and R V in one launch, one wave per SIMD)"
         elif fused:
             kern, what = "flash_kv_kernel", "flash_kv_kernel (last R-update: logits, R K, c_L and R V in one launch)"
@@ -384,7 +384,8 @@ def main() -> int:
         if "r_update" in phases:
             # the fitting sweeps' R-update (logits + R K), one launch each
             fl2, t2 = 4.0 * BH * T * b * b * d, phases["r_update"]
-            roofline["fitting_r_update"] = {"kernel": "flash2_kernel (logits + R K)" if variant == 1 else "flash_kernel (logits + R K)",
+            two_tiles = variant == 1 or (variant == 2 and d == 64)
+            roofline["fitting_r_update"] = {"kernel": "flash2_kernel (logits + R K)" if two_tiles else "flash_kernel (logits + R K)",
                                             "flops_per_launch": fl2,
                                             "ms_per_launch": t2, "achieved": fl2 / (t2 * 1e-3) / 1e12,
                                             "frac": fl2 / (t2 * 1e-3) / 1e12 / BF16_MFMA_PEAK_TFLOPS}
@@ -421,6 +422,14 @@ def main() -> int:
     torch.cuda.synchronize()
     hbm_phase["permute_tokens"] = hbm("vmonarch_permute_tokens, frame-major -> position-major copy of q",
                                       2.0 * BH * N * d * elem, pe[0].elapsed_time(pe[1]) / nperm)
+    # context, not a kernel of this library: the runtime's own device-to-device copy of the same tensor
+    pe[0].record()
+    for _ in range(nperm):
+        perm_out.copy_(tq)
+    pe[1].record()
+    torch.cuda.synchronize()
+    hbm_phase["device_copy"] = hbm("device-to-device copy of q by the HIP runtime (context: what a plain copy reaches)",
+                                   2.0 * BH * N * d * elem, pe[0].elapsed_time(pe[1]) / nperm)
     del perm_out
 
     if args.copy_calibration:

@@ -97,10 +97,12 @@ int vmonarch_get_fused_apply(void);
 int vmonarch_set_manual_control(int cr_control, int cl_control, float cl_value);
 int vmonarch_get_manual_control(int* cr_control, int* cl_control, float* cl_value);
 
-/* Which bf16 MFMA kernel runs an R-update: 0 (default) the kernels with two waves per SIMD and one
- * 32-query tile per wave; 1 the kernel with one wave per SIMD and two query tiles per wave, whose
+/* Which bf16 MFMA kernel runs an R-update: 0 the kernels with two waves per SIMD and one 32-query
+ * tile per wave; 1 the kernel with one wave per SIMD and two query tiles per wave, whose
  * accumulators live in accumulation registers (measured a few per cent faster for the update with
- * values and slower without).  Same results up to rounding order.  Process-wide. */
+ * values and, at d = 64, without; slower without values at d = 128); 2 (default) each update on
+ * the kernel measured faster for it: that of 1 for the update with values and for d = 64, those
+ * of 0 for the update without values at d = 128.  Same results up to rounding order.  Process-wide. */
 int vmonarch_set_flash_variant(int variant);
 int vmonarch_get_flash_variant(void);
 

@@ -35,7 +35,7 @@ float g_cl_value = NAN;  // NaN: -log(b), the c_L of a uniform row of R
 int g_entropy_mode = VMONARCH_ENTROPY_ONLINE;
 // which bf16 MFMA kernel runs an R-update: 0 the two-waves-per-SIMD kernels (flash.hip, flash_kv.hip; the faster
 // ones as measured on MI355X), 1 the one-wave-per-SIMD kernel with two query tiles per wave (flash2.hip)
-int g_flash_variant = 0;
+int g_flash_variant = 2;
 
 std::mutex g_ws_mutex;
 void* g_user_ws = nullptr;
@@ -249,7 +249,8 @@ int r_update_any<bf16_t>(const bf16_t* aR, const float* cR, const bf16_t* k, con
                          bf16_t* y, float* lse, const Dims& dm, float row_scale, float cr_min, const Settings& cfg,
                          hipStream_t st) {
   hipError_t e;
-  if (flash_supported(dm) && cfg.flash_variant == 1)
+  // variant 2: every update on the kernel that was measured faster for it
+  if (flash_supported(dm) && (cfg.flash_variant == 1 || (cfg.flash_variant == 2 && (v != nullptr || dm.d == 64))))
     e = launch_r_update_flash2(aR, cR, k, v, aL, cL, y, lse, dm, row_scale, cr_min, cfg.entropy_mode, st);
   else if (flash_supported(dm))
     e = launch_r_update_flash(aR, cR, k, v, aL, cL, y, lse, dm, row_scale, cr_min, cfg.entropy_mode, cfg.fused_apply != 0, st);
@@ -527,7 +528,7 @@ int vmonarch_set_fused_apply(int enable) {
 int vmonarch_get_fused_apply(void) { return g_fused_apply; }
 
 int vmonarch_set_flash_variant(int variant) {
-  if (variant != 0 && variant != 1) return fail(VMONARCH_ERR_INVALID_ARG, "flash variant is 0 or 1");
+  if (variant < 0 || variant > 2) return fail(VMONARCH_ERR_INVALID_ARG, "flash variant is 0, 1 or 2");
   g_flash_variant = variant;
   return VMONARCH_OK;
 }
@@ -632,7 +633,7 @@ static int settings_from_options(const vmonarch_options* o, Settings* cfg) {
   if (!(o->cr_min >= 0.f)) return fail(VMONARCH_ERR_INVALID_ARG, "options.cr_min must be >= 0");
   if (o->entropy_mode != VMONARCH_ENTROPY_ONLINE && o->entropy_mode != VMONARCH_ENTROPY_IDENTITY)
     return fail(VMONARCH_ERR_INVALID_ARG, "unknown options.entropy_mode %d", o->entropy_mode);
-  if (o->flash_variant != 0 && o->flash_variant != 1) return fail(VMONARCH_ERR_INVALID_ARG, "options.flash_variant is 0 or 1");
+  if (o->flash_variant < 0 || o->flash_variant > 2) return fail(VMONARCH_ERR_INVALID_ARG, "options.flash_variant is 0, 1 or 2");
   if (o->cr_control < VMONARCH_CONTROL_NONE || o->cr_control > VMONARCH_CONTROL_ALL_FRAMES ||
       o->cl_control < VMONARCH_CONTROL_NONE || o->cl_control > VMONARCH_CONTROL_ALL_FRAMES)
     return fail(VMONARCH_ERR_INVALID_ARG, "options control modes are 0 (none), 1 (first frame), 2 (all frames)");
@@ -658,7 +659,7 @@ int vmonarch_options_init(vmonarch_options* options) {
   options->cr_min = 0.1f;
   options->entropy_mode = VMONARCH_ENTROPY_ONLINE;
   options->fused_apply = 1;
-  options->flash_variant = 0;
+  options->flash_variant = 2;
   options->cr_control = VMONARCH_CONTROL_NONE;
   options->cl_control = VMONARCH_CONTROL_NONE;
   options->cl_value = NAN;

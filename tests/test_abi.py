@@ -47,7 +47,7 @@ def test_host_only_entry_points():
     # per-call options: defaults, and validation without a GPU (nothing is launched on a bad field)
     o = binding.default_options()
     assert o.struct_bytes == ctypes.sizeof(binding.Options) and abs(o.cr_min - 0.1) < 1e-7
-    assert (o.entropy_mode, o.fused_apply, o.flash_variant, o.cr_control, o.cl_control) == (0, 1, 0, 0, 0)
+    assert (o.entropy_mode, o.fused_apply, o.flash_variant, o.cr_control, o.cl_control) == (0, 1, 2, 0, 0)
     assert o.cl_value != o.cl_value and not o.workspace and o.workspace_bytes == 0
     one = ctypes.c_void_p(256)   # never dereferenced: validation fails first
     o.entropy_mode = 7

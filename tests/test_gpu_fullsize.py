@@ -133,15 +133,18 @@ def test_headline_long_video_sampled_positions_and_invariants(env):
     assert torch.equal(out, binding.attention(tq, tk, tv, wl.T, wl.Hs, wl.Ws, wl.iters, wl.recompute))
 
 
-def test_headline_shape_with_the_one_wave_per_simd_kernel(env):
-    """The same workload with both R-updates on the kernel that keeps one wave per SIMD and two query tiles per wave."""
+@pytest.mark.parametrize("variant", [0, 1])
+def test_headline_shape_with_one_kernel_family_for_both_updates(env, variant):
+    """The default gives each R-update the kernel measured faster for it; here both updates run on the kernels
+    with two waves per SIMD (0), then both on the kernel with one wave per SIMD and two query tiles per wave (1)."""
     torch, binding, dev = env
-    binding.set_flash_variant(1)
+    default = binding.get_flash_variant()
+    binding.set_flash_variant(variant)
     try:
         _run_workload(env, "long-81x28x52", [2, 9], 24, 6)
         _run_workload(env, "wan1.3b-480p", [0], 48, 1)
     finally:
-        binding.set_flash_variant(0)
+        binding.set_flash_variant(default)
 
 
 def test_headline_unclamped_cr_sums_to_frame_count(env):
