@@ -62,8 +62,8 @@ def test_wan_480p_clip_sampled_positions(env):
 
 
 def test_wan_720p_clip_sampled_positions(env):
-    """b = 3600 (15 query blocks, ragged), T = 21 padded to 32 in the temporal pass; 2 of the 40 heads."""
-    _run_workload(env, "wan14b-720p", [0, 39], 16, 3)
+    """b = 3600 (15 query blocks, ragged), T = 21 padded to 32 in the temporal pass; 3 of the 40 heads."""
+    _run_workload(env, "wan14b-720p", [0, 21, 39], 24, 3)
 
 
 @pytest.mark.parametrize("iters", [1, 3])
@@ -102,10 +102,10 @@ def test_permutation_copy_at_headline_shape(env):
         assert torch.equal(binding.permute_tokens(got, wl.T, wl.Hs, wl.Ws, False), x)
 
 
-def test_million_token_stress_single_head(env):
+def test_million_token_stress_two_heads(env):
     """N = 991,440 tokens: b = 12,240 keys per frame (192 key tiles, ragged), one sweep, no
-    recomputation; one of the 12 heads (row offsets beyond 2^31 bytes within the head)."""
-    _run_workload(env, "stress-1m", [5], 8, 4)
+    recomputation; two of the 12 heads (row offsets beyond 2^31 bytes within the head)."""
+    _run_workload(env, "stress-1m", [5, 11], 16, 4)
 
 
 def test_paper_kernel_benchmark_shape_sampled_positions(env):
