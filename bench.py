@@ -125,6 +125,8 @@ def sweep_frames(args) -> int:
 
     dev = torch.device("cuda:0")
     binding.lib()
+    if args.flash_variant is not None:
+        binding.set_flash_variant(args.flash_variant)
     heads, Hs, Ws, d = 12, 28, 52, 128
     for T in range(20, 49, 4):
         wl = synth.Workload(f"sweep-{T}x28x52", 20 + T, 1, heads, T, Hs, Ws, d, "bf16", 2, True)
@@ -163,6 +165,8 @@ def sweep_budget(args) -> int:
 
     dev = torch.device("cuda:0")
     binding.lib()
+    if args.flash_variant is not None:
+        binding.set_flash_variant(args.flash_variant)
     for m, b in synth.BUDGET_SPLITS:
         wl = synth.WORKLOADS[f"budget-{m}x{b}"]
         q, k, v = synth.make_inputs(wl)

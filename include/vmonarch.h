@@ -101,8 +101,8 @@ int vmonarch_get_manual_control(int* cr_control, int* cl_control, float* cl_valu
  * tile per wave; 1 the kernel with one wave per SIMD and two query tiles per wave, whose
  * accumulators live in accumulation registers (measured a few per cent faster for the update with
  * values and, at d = 64, without; slower without values at d = 128); 2 (default) each update on
- * the kernel measured faster for it: that of 1 for the update with values and for d = 64, those
- * of 0 for the update without values at d = 128.  Same results up to rounding order.  Process-wide. */
+ * the kernel measured faster for it: that of 1 for the update with values (frames of more than
+ * 128 tokens) and for d = 64, those of 0 otherwise.  Same results up to rounding order.  Process-wide. */
 int vmonarch_set_flash_variant(int variant);
 int vmonarch_get_flash_variant(void);
 

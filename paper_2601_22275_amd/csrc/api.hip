@@ -249,8 +249,12 @@ int r_update_any<bf16_t>(const bf16_t* aR, const float* cR, const bf16_t* k, con
                          bf16_t* y, float* lse, const Dims& dm, float row_scale, float cr_min, const Settings& cfg,
                          hipStream_t st) {
   hipError_t e;
-  // variant 2: every update on the kernel that was measured faster for it
-  if (flash_supported(dm) && (cfg.flash_variant == 1 || (cfg.flash_variant == 2 && (v != nullptr || dm.d == 64))))
+  // variant 2: every update on the kernel that was measured faster for it.  With values: the two-tile kernel, unless a
+  // frame has at most 128 tokens (its 256-row query blocks would be mostly padding; the wave-pair kernel's hold 128).
+  // Without values: the two-tile kernel at d = 64, the one-tile kernel at d = 128.
+  const bool two_tiles = cfg.flash_variant == 1 ||
+                         (cfg.flash_variant == 2 && (v != nullptr ? dm.b > 128 : dm.d == 64));
+  if (flash_supported(dm) && two_tiles)
     e = launch_r_update_flash2(aR, cR, k, v, aL, cL, y, lse, dm, row_scale, cr_min, cfg.entropy_mode, st);
   else if (flash_supported(dm))
     e = launch_r_update_flash(aR, cR, k, v, aL, cL, y, lse, dm, row_scale, cr_min, cfg.entropy_mode, cfg.fused_apply != 0, st);
