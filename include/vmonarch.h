@@ -82,9 +82,11 @@ int vmonarch_set_cr_min(float cr_min);
 float vmonarch_get_cr_min(void);
 
 /* bf16 MFMA R-update with values (the last sweep; vmonarch_r_update[_lse] with v != NULL) and online
- * entropy: 1 (default) forms alpha_L, c_L and y = R V from one evaluation of the logits and the
- * softmax, two waves sharing a query tile; 0 runs one pass for alpha_L / c_L and a second for y.
- * Same results up to rounding order.  Process-wide. */
+ * entropy, when it runs on the kernels with two waves per SIMD (flash variant 0, and variant 2 for
+ * frames of at most 128 tokens): 1 (default) forms alpha_L, c_L and y = R V from one evaluation of
+ * the logits and the softmax, two waves sharing a query tile; 0 runs one pass for alpha_L / c_L and
+ * a second for y.  The kernel with one wave per SIMD (see vmonarch_set_flash_variant) always takes
+ * one pass.  Same results up to rounding order.  Process-wide. */
 int vmonarch_set_fused_apply(int enable);
 int vmonarch_get_fused_apply(void);
 
