@@ -326,25 +326,37 @@ __global__ void __launch_bounds__(64 * W2) flash2_kernel(FlashParams P) {
   bf16x2 ones2;
   ones2[0] = (__bf16)1.0f;
   ones2[1] = (__bf16)1.0f;
-  // two scores of one query tile: t = s sc - m, p = 2^t, bf16 pair, l += rounded p, h += rounded p t
-  auto score_pair = [&](auto kc, f32x16 (&scur)[Q2], bf16x8 (&pbcur)[Q2][2]) __attribute__((always_inline)) {
+  // Two scores of one query tile: t = s sc - m, p = 2^t, bf16 pair, l += rounded p, h += rounded p t.  The three
+  // stages of a pair (scale, exponent, the rest) are dependent instructions; each stage goes to an MFMA slot of its
+  // own (the stages that share a slot then belong to different pairs and issue back to back), so that a single
+  // wave does not sit out the latency of its own chain.
+  float tq[2][2], pq[2][2];  // in flight between the stages, by parity of the pair
+  auto score_scale = [&](auto kc, f32x16 (&scur)[Q2]) __attribute__((always_inline)) {
     constexpr int K = decltype(kc)::value;  // 0 .. 15
     constexpr int qt = K & 1;
     constexpr int j = K >> 1;
-    const float t0 = __builtin_fmaf(scur[qt][2 * j], sc[qt], -msc[qt]);
-    const float t1 = __builtin_fmaf(scur[qt][2 * j + 1], sc[qt], -msc[qt]);
-    const float p0 = __builtin_amdgcn_exp2f(t0);
-    const float p1 = __builtin_amdgcn_exp2f(t1);
+    tq[K & 1][0] = __builtin_fmaf(scur[qt][2 * j], sc[qt], -msc[qt]);
+    tq[K & 1][1] = __builtin_fmaf(scur[qt][2 * j + 1], sc[qt], -msc[qt]);
+  };
+  auto score_exp = [&](auto kc) __attribute__((always_inline)) {
+    constexpr int K = decltype(kc)::value;
+    pq[K & 1][0] = __builtin_amdgcn_exp2f(tq[K & 1][0]);
+    pq[K & 1][1] = __builtin_amdgcn_exp2f(tq[K & 1][1]);
+  };
+  auto score_sums = [&](auto kc, bf16x8 (&pbcur)[Q2][2]) __attribute__((always_inline)) {
+    constexpr int K = decltype(kc)::value;
+    constexpr int qt = K & 1;
+    constexpr int j = K >> 1;
     bf16x2 pr;
-    pr[0] = (__bf16)p0;  // round to nearest even; the pair is one v_cvt_pk_bf16_f32
-    pr[1] = (__bf16)p1;
+    pr[0] = (__bf16)pq[K & 1][0];  // round to nearest even; the pair is one v_cvt_pk_bf16_f32
+    pr[1] = (__bf16)pq[K & 1][1];
     ltil[qt] = __builtin_amdgcn_fdot2_f32_bf16(pr, ones2, ltil[qt], false);
     if (ENT == 1) {
       // h with the same rounded weights that l and the products carry
       uint32_t w;
       __builtin_memcpy(&w, &pr, 4);
-      hsum[qt] = __builtin_fmaf(__uint_as_float(w << 16), t0, hsum[qt]);
-      hsum[qt] = __builtin_fmaf(__uint_as_float(w & 0xffff0000u), t1, hsum[qt]);
+      hsum[qt] = __builtin_fmaf(__uint_as_float(w << 16), tq[K & 1][0], hsum[qt]);
+      hsum[qt] = __builtin_fmaf(__uint_as_float(w & 0xffff0000u), tq[K & 1][1], hsum[qt]);
     }
     pbcur[qt][j >> 2][2 * (j & 3)] = pr[0];
     pbcur[qt][j >> 2][2 * (j & 3) + 1] = pr[1];
@@ -417,10 +429,18 @@ __global__ void __launch_bounds__(64 * W2) flash2_kernel(FlashParams P) {
       static_for<0, 2>([&](auto qc) {
         constexpr int SL = 2 * GI + decltype(qc)::value;
         issue(gc, qc, snext, pbprev);
-        // score pairs dealt evenly over the slots: pair k goes to slot floor(k NSL / 16)
+        // score pairs dealt evenly over the slots: pair k starts in slot floor(k NSL / 16), its exponents follow one
+        // slot later and its sums two slots later (both clamped to the step's last slot).  Pairs in ascending
+        // order, stages in their own order: a pair's stages that meet in one slot stay in sequence, and the sums
+        // of pair k come before pair k + 2 reuses its buffers (it starts at least two slots after pair k).
         static_for<0, 16>([&](auto kc) {
           constexpr int K = decltype(kc)::value;
-          if constexpr ((K * NSL) / 16 == SL) score_pair(kc, scur, pbcur);
+          constexpr int S0 = (K * NSL) / 16;
+          constexpr int S1 = S0 + 1 < NSL ? S0 + 1 : NSL - 1;
+          constexpr int S2 = S0 + 2 < NSL ? S0 + 2 : NSL - 1;
+          if constexpr (S0 == SL) score_scale(kc, scur);
+          if constexpr (S1 == SL) score_exp(kc);
+          if constexpr (S2 == SL) score_sums(kc, pbcur);
         });
         if constexpr (SL == SLOT_MAX0) row_max(std::integral_constant<int, 0>{}, snext);
         if constexpr (SL == SLOT_MAX1) row_max(std::integral_constant<int, 1>{}, snext);
