@@ -395,7 +395,8 @@ def main() -> int:
                                             "frac": fl2 / (t2 * 1e-3) / 1e12 / BF16_MFMA_PEAK_TFLOPS}
         if "first_frame" in phases:
             fl3, t3 = 4.0 * BH * b * N * d, phases["first_frame"]
-            roofline["first_frame"] = {"kernel": "flash_kernel over key ranges + merge (exact attention of frame 0)",
+            ff_kernel = "flash2_kernel" if bf16 and d in (64, 128) and variant != 0 else "flash_kernel"
+            roofline["first_frame"] = {"kernel": ff_kernel + " over key ranges + merge (exact attention of frame 0)",
                                        "flops_per_launch": fl3, "ms_per_launch": t3,
                                        "achieved": fl3 / (t3 * 1e-3) / 1e12,
                                        "frac": fl3 / (t3 * 1e-3) / 1e12 / BF16_MFMA_PEAK_TFLOPS}

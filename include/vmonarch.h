@@ -104,7 +104,9 @@ int vmonarch_get_manual_control(int* cr_control, int* cl_control, float* cl_valu
  * accumulators live in accumulation registers (measured a few per cent faster for the update with
  * values and, at d = 64, without; slower without values at d = 128); 2 (default) each update on
  * the kernel measured faster for it: that of 1 for the update with values (frames of more than
- * 128 tokens) and for d = 64, those of 0 otherwise.  Same results up to rounding order.  Process-wide. */
+ * 128 tokens) and for d = 64, those of 0 otherwise.  Exact attention of a contiguous row range
+ * (first frame, vmonarch_recompute_rows) runs on the kernel of 1 unless the variant is 0; a row
+ * list (vmonarch_recompute_tokens) and the sink averaging always run on the kernels of 0.  Same results up to rounding order.  Process-wide. */
 int vmonarch_set_flash_variant(int variant);
 int vmonarch_get_flash_variant(void);
 

@@ -289,19 +289,20 @@ int l_update_any<bf16_t>(const bf16_t* q, const bf16_t* aL, const float* cL, con
 
 template <typename E>
 int first_frame_any(const E* q, const E* k, const E* v, E* out, float* lse, void* scratch, size_t scratch_bytes,
-                    const Dims& dm, int nrows, const int* rows, hipStream_t st);
+                    const Dims& dm, int nrows, const int* rows, int flash_variant, hipStream_t st);
 template <>
 int first_frame_any<float>(const float* q, const float* k, const float* v, float* out, float* lse, void*, size_t,
-                           const Dims& dm, int nrows, const int* rows, hipStream_t st) {
+                           const Dims& dm, int nrows, const int* rows, int, hipStream_t st) {
   hipError_t e = launch_first_frame_generic<float>(q, k, v, out, lse, dm, nrows, rows, st);
   return e == hipSuccess ? VMONARCH_OK : hip_fail(e, "first_frame (plain-ALU f32) launch");
 }
 template <>
 int first_frame_any<bf16_t>(const bf16_t* q, const bf16_t* k, const bf16_t* v, bf16_t* out, float* lse, void* scratch,
-                            size_t scratch_bytes, const Dims& dm, int nrows, const int* rows, hipStream_t st) {
+                            size_t scratch_bytes, const Dims& dm, int nrows, const int* rows, int flash_variant,
+                            hipStream_t st) {
   hipError_t e;
   if (flash_supported(dm))
-    e = launch_first_frame_flash(q, k, v, out, lse, scratch, scratch_bytes, dm, nrows, rows, st);
+    e = launch_first_frame_flash(q, k, v, out, lse, scratch, scratch_bytes, dm, nrows, rows, flash_variant != 0, st);
   else
     e = launch_first_frame_generic<bf16_t>(q, k, v, out, lse, dm, nrows, rows, st);
   return e == hipSuccess ? VMONARCH_OK : hip_fail(e, "first_frame (bf16) launch");
@@ -394,7 +395,7 @@ int attention_impl(const void* q_, const void* k_, const void* v_, void* out_, i
     if (rc) return rc;
   } else if (recompute) {
     phase_mark(st, "first_frame");
-    rc = first_frame_any<E>(q, k, v, out, nullptr, ws + w.ff, w.total - w.ff, dm, dm.b, nullptr, st);
+    rc = first_frame_any<E>(q, k, v, out, nullptr, ws + w.ff, w.total - w.ff, dm, dm.b, nullptr, cfg.flash_variant, st);
     if (rc) return rc;
   }
   phase_mark(st, nullptr);
@@ -457,7 +458,8 @@ int first_frame_impl(const void* q, const void* k, const void* v, void* out, flo
   }
   // the kernels index query rows from the pointers they are given: hand them the first row of the range
   return first_frame_any<E>((const E*)q + row_begin * d, (const E*)k, (const E*)v, (E*)out + row_begin * d,
-                            lse ? lse + row_begin : nullptr, scratch, sb, dm, nrows, nullptr, (hipStream_t)stream);
+                            lse ? lse + row_begin : nullptr, scratch, sb, dm, nrows, nullptr, g_flash_variant,
+                            (hipStream_t)stream);
 }
 
 // Exact attention of a list of rows (the same list for every head).
@@ -481,7 +483,7 @@ int recompute_tokens_impl(const void* q, const void* k, const void* v, void* out
     }
   }
   return first_frame_any<E>((const E*)q, (const E*)k, (const E*)v, (E*)out, nullptr, scratch, sb, dm, nrows, rows,
-                            (hipStream_t)stream);
+                            g_flash_variant, (hipStream_t)stream);
 }
 
 template <typename E>
@@ -788,7 +790,8 @@ int vmonarch_recompute_rows_noalloc(const void* q, const void* k, const void* v,
   }
   // every partial the merge reads is written by the key-range pass of the same call: nothing to clear
   return first_frame_any<bf16_t>((const bf16_t*)q + row_begin * d, (const bf16_t*)k, (const bf16_t*)v,
-                                 (bf16_t*)out + row_begin * d, nullptr, sp, sb, dm, nrows, nullptr, (hipStream_t)stream);
+                                 (bf16_t*)out + row_begin * d, nullptr, sp, sb, dm, nrows, nullptr, g_flash_variant,
+                                 (hipStream_t)stream);
 }
 
 int vmonarch_sink_average(const void* q, const void* k, const void* v, void* out, int B, int heads, int T, int Hs,

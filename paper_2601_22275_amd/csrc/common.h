@@ -126,10 +126,15 @@ hipError_t launch_r_update_flash2(const bf16_t* aR, const float* cR, const bf16_
 // exact attention of nrows query rows per head (starting where q / out / lse point) over all N keys
 size_t first_frame_flash_scratch_bytes(const Dims& dm, int nrows);
 // rows (device, may be null): a list of nrows row numbers within a head, used for every head; q / out / lse then
-// point at row 0; entries outside [0, N) are skipped
+// point at row 0; entries outside [0, N) are skipped.  two_tile: contiguous rows go to flash2.hip's kernel
 hipError_t launch_first_frame_flash(const bf16_t* q, const bf16_t* k, const bf16_t* v, bf16_t* out, float* lse,
                                     void* scratch, size_t scratch_bytes, const Dims& dm, int nrows, const int* rows,
-                                    hipStream_t st);
+                                    bool two_tile, hipStream_t st);
+// flash2.hip : the same pass (contiguous rows only) on the kernel with two query tiles per wave; the caller has cut the
+// keys into ns ranges of keys_per_split and owns the partial-result buffers
+hipError_t launch_first_frame_flash2(const bf16_t* q, const bf16_t* k, const bf16_t* v, bf16_t* out, float* lse,
+                                     float* part_o, float* part_lse, const Dims& dm, int nrows, int ns,
+                                     int keys_per_split, hipStream_t st);
 
 // the temporal factor for any T <= 8128 through the same kernel (see flash.hip); lse_scratch: BH * N floats, fitting sweep only
 bool temporal_flash_supported(const Dims& dm);

@@ -689,6 +689,32 @@ hipError_t launch_flash2(const FlashParams& P, hipStream_t st) {
 
 int flash2_query_block() { return BQ2; }
 
+// Exact attention of a contiguous run of nrows query rows per head over all keys (Sec. 3.3) on this kernel, the keys
+// cut into `ns` ranges of keys_per_split (a multiple of the tile) whose partial results go to part_o / part_lse
+// for the merge (ns == 1: straight to out / lse).  Same 256-row query blocks and partial-result layout as the
+// one-tile kernel's pass.
+hipError_t launch_first_frame_flash2(const bf16_t* q, const bf16_t* k, const bf16_t* v, bf16_t* out, float* lse,
+                                     float* part_o, float* part_lse, const Dims& dm, int nrows, int ns,
+                                     int keys_per_split, hipStream_t st) {
+  FlashParams P = {};
+  P.q = q; P.k = k; P.v = v; P.outv = out; P.lse = lse; P.part_o = part_o; P.part_lse = part_lse;
+  P.q_rows_per_problem = dm.N; P.k_rows_per_problem = dm.N;
+  P.nq = nrows;
+  P.nk = (int)dm.N;
+  P.nqb = (nrows + BQ2 - 1) / BQ2;
+  P.nsplit = ns;
+  P.keys_per_split = keys_per_split;
+  const long long total = (long long)dm.BH * P.nqb * ns;
+  if (total > 0x3fffffffLL) return hipErrorInvalidValue;
+  P.total_blocks = (int)total;
+  P.blocks_per_xcd = (P.total_blocks + 7) / 8;
+  P.row_scale = 1.0f / sqrtf((float)dm.d);
+  P.cr_min = 0.f;
+  const bool split = ns > 1;
+  if (dm.d == 128) return split ? launch_flash2<128, false, true, 0, true>(P, st) : launch_flash2<128, false, true, 0, false>(P, st);
+  return split ? launch_flash2<64, false, true, 0, true>(P, st) : launch_flash2<64, false, true, 0, false>(P, st);
+}
+
 // One R-update on the one-wave-per-SIMD kernel: alpha_L, c_L (and lse if not null), plus y when v is given.
 hipError_t launch_r_update_flash2(const bf16_t* aR, const float* cR, const bf16_t* k, const bf16_t* v, bf16_t* aL,
                                   float* cL, bf16_t* y, float* lse, const Dims& dm, float row_scale, float cr_min,
