@@ -310,10 +310,21 @@ def test_l_update_matches_oracle(env, T, Hs, Ws, d, dt, final):
 
 
 # ------------------------------------------------------------------ first-frame recomputation
+@pytest.fixture(params=["two-tile", "one-tile"])
+def first_frame_kernel(request, env):
+    """Exact attention of contiguous rows runs on the kernel with two query tiles per wave by default and on the
+    one-tile kernel when flash variant 0 is selected (bf16, d = 64 or 128; other cases take neither)."""
+    binding = env[1]
+    default = binding.get_flash_variant()
+    binding.set_flash_variant(0 if request.param == "one-tile" else default)
+    yield request.param
+    binding.set_flash_variant(default)
+
+
 @pytest.mark.parametrize("T,Hs,Ws,d,dt", [(4, 4, 4, 32, "f32"), (3, 5, 5, 96, "bf16"), (1, 3, 3, 128, "bf16"),
                                            (4, 10, 30, 128, "bf16"), (9, 7, 9, 128, "bf16"),
                                            (3, 5, 5, 64, "bf16"), (4, 10, 30, 64, "bf16"), (9, 7, 9, 64, "bf16")])
-def test_first_frame_attention_matches_oracle(env, T, Hs, Ws, d, dt):
+def test_first_frame_attention_matches_oracle(env, T, Hs, Ws, d, dt, first_frame_kernel):
     torch, binding, dev = env
     bf16 = dt == "bf16"
     b, heads = Hs * Ws, 2
@@ -331,7 +342,7 @@ def test_first_frame_attention_matches_oracle(env, T, Hs, Ws, d, dt):
 
 
 @pytest.mark.parametrize("T,b", [(15, 64), (16, 64), (17, 64), (33, 40), (64, 33), (130, 31), (9, 300)])
-def test_first_frame_key_range_splits(env, T, b):
+def test_first_frame_key_range_splits(env, T, b, first_frame_kernel):
     """N = T b keys around the points where the pass starts splitting the key range (at least 8 tiles per
     range) and where ranges end in ragged tiles."""
     torch, binding, dev = env
