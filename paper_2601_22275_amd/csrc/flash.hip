@@ -636,7 +636,8 @@ hipError_t launch_first_frame_flash(const bf16_t* q, const bf16_t* k, const bf16
   const bool d128 = dm.d == 128;
   // contiguous rows can run on the kernel with two query tiles per wave (same blocks, ranges and partial results;
   // measured 2 .. 3 % faster on the long key loops of this pass); a row list is gathered by this file's kernel only
-  const bool ff2 = two_tile && row_list == nullptr;
+  // (the key ranges and the partial-result buffers above are sized for this file's query blocks: the other kernel's must match)
+  const bool ff2 = two_tile && row_list == nullptr && flash2_query_block() == BQ;
   if (ns == 1) {
     if (ff2) return launch_first_frame_flash2(q, k, v, out, lse, nullptr, nullptr, dm, nrows, 1, P.keys_per_split, st);
     return d128 ? launch_flash<128, false, true, 0, false>(P, st) : launch_flash<64, false, true, 0, false>(P, st);
