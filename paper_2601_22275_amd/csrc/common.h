@@ -130,6 +130,7 @@ size_t first_frame_flash_scratch_bytes(const Dims& dm, int nrows);
 hipError_t launch_first_frame_flash(const bf16_t* q, const bf16_t* k, const bf16_t* v, bf16_t* out, float* lse,
                                     void* scratch, size_t scratch_bytes, const Dims& dm, int nrows, const int* rows,
                                     bool two_tile, hipStream_t st);
+int flash2_query_block();  // query rows per workgroup of flash2.hip's kernel
 // flash2.hip : the same pass (contiguous rows only) on the kernel with two query tiles per wave; the caller has cut the
 // keys into ns ranges of keys_per_split and owns the partial-result buffers
 hipError_t launch_first_frame_flash2(const bf16_t* q, const bf16_t* k, const bf16_t* v, bf16_t* out, float* lse,
