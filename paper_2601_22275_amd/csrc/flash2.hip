@@ -44,6 +44,12 @@ constexpr int BQ2 = 32 * Q2 * W2;  // query rows per workgroup
 // registers and pass through ordinary ones to be rescaled), and in the last sweep's update, where c_R
 // sharpens some rows tenfold, a margin of 2^8 would move one in most steps.
 constexpr float RESCALE_TH2 = 32.0f;
+// Where a moving reference is put: this far (log2 units) above the row maximum that moved it, the first one
+// included.  Any reference gives the same results (the sums and the accumulators carry the common factor
+// 2^-reference, and fp32 / bf16 have exponent range to spare: the largest probability of a row is then 2^-64, keys
+// more than 2^-62 below the row maximum flush to zero); a high one makes later moves rare, which matters where
+// attention is sharp (logits many times their usual spread: row maxima then jump by more than 2^32 from tile to tile).
+constexpr float HEADROOM2 = 64.0f;
 
 __device__ __forceinline__ uint32_t avg_bf16x2(uint32_t a, uint32_t b) {
   const float lo = 0.5f * (__uint_as_float(a << 16) + __uint_as_float(b << 16));
@@ -376,7 +382,9 @@ __global__ void __launch_bounds__(64 * W2) flash2_kernel(FlashParams P) {
     moved = __any(grow);
 #pragma unroll
     for (int qt = 0; qt < Q2; ++qt) {
-      mpend[qt] = moved ? fmaxf(msc[qt], cand[qt]) : msc[qt];
+      // a reference that moves goes HEADROOM2 above the row's maximum: the next move then needs a maximum
+      // 2^(HEADROOM2 + RESCALE_TH2) times the present one
+      mpend[qt] = moved ? fmaxf(msc[qt], cand[qt] + HEADROOM2) : msc[qt];
       asm volatile("" : "+v"(mpend[qt]));
     }
   };

@@ -181,12 +181,14 @@ def test_r_update_random_shapes_both_forms(env, seed, fused):
         assert U.max_abs(gcL[h].reshape(T, b), rcL.T) <= 2e-2, (T, b, d, with_cr)
 
 
+@pytest.mark.parametrize("spike", [7.0, 72.0])
 @pytest.mark.parametrize("d", [64, 128])
-def test_r_update_when_the_reference_max_moves_in_every_tile(env, d, fused):
+def test_r_update_when_the_reference_max_moves_in_every_tile(env, d, fused, spike):
     """Keys with ever larger logits in later tiles, one spike key per tile, and queries that respond to the
-    spikes with different strength: the kernels' reference maxima move (by more than 2^8) in almost every tile,
-    in the wave that produces the probabilities and in the one that adopts them, while the mass below the
-    spikes still matters for many rows."""
+    spikes with different strength: the kernels' reference maxima move in almost every tile, in the wave that
+    produces the probabilities and in the one that adopts them, while the mass below the spikes still matters for
+    many rows.  Spikes of 7 per tile raise the strongest rows' maxima by 2^8 per tile (the margin of the kernels
+    with two waves per SIMD), spikes of 72 by more than 2^56 (margin plus headroom of the kernel with one)."""
     torch, binding, dev = env
     b = 600                                           # 10 key tiles, ragged; 5 query blocks of 128
     rng = np.random.default_rng(77 + d)
@@ -195,7 +197,7 @@ def test_r_update_when_the_reference_max_moves_in_every_tile(env, d, fused):
     qf[:, 0] = np.linspace(0.0, 9.0, b)[rng.permutation(b)]   # response of a query to the spikes
     kf[:, 0] = 0.0
     for t, l in enumerate(range(17, b, 61)):                   # one spike every 61 keys, growing
-        kf[l, 0] = 7.0 * (t + 1)
+        kf[l, 0] = spike * (t + 1)
     vf = rng.normal(size=(b, d))
     q, k, v = (synth.f32_to_bf16_bits(x.astype(np.float32)) for x in (qf, kf, vf))
     row_scale, cr_min = 1.0 / math.sqrt(d), 0.1
