@@ -128,7 +128,7 @@ def sweep_frames(args) -> int:
     if args.flash_variant is not None:
         binding.set_flash_variant(args.flash_variant)
     heads, Hs, Ws, d = 12, 28, 52, 128
-    for T in range(20, 49, 4):
+    for T in list(range(20, 49, 4)) + [81]:   # the figure's range, then the headline length
         wl = synth.Workload(f"sweep-{T}x28x52", 20 + T, 1, heads, T, Hs, Ws, d, "bf16", 2, True)
         q, k, v = synth.make_inputs(wl)
         tq, tk, tv = (torch.from_numpy(x).to(dev).view(torch.bfloat16).view(1, heads, wl.N, d) for x in (q, k, v))
