@@ -504,6 +504,51 @@ E2E = [
 ]
 
 
+@pytest.mark.parametrize("seed", [11, 12, 13])
+def test_attention_random_configurations(env, seed):
+    """Seeded random (T, Hs, Ws, d, sweeps, recomputation mode, kernel family) through the whole path, every output
+    element against the oracle: 12 configurations per seed, frames up to 300 (so that all three forms of the temporal
+    factor occur), ragged everything."""
+    torch, binding, dev = env
+    rng = np.random.default_rng(seed)
+    default = binding.get_flash_variant()
+    done = 0
+    try:
+        while done < 12:
+            d = int(rng.choice([64, 128]))
+            T = int(rng.integers(1, 40)) if rng.random() < 0.85 else int(rng.integers(129, 300))
+            Hs, Ws = int(rng.integers(1, 24)), int(rng.integers(1, 40))
+            b = Hs * Ws
+            if T * b > 40000 or T * b * b > 2e7:
+                continue
+            iters, rec, variant = int(rng.integers(1, 4)), int(rng.choice([0, 1, 1, 2])), int(rng.choice([0, 1, 2, 2]))
+            data = U.structured_heads(T, Hs, Ws, d, 60 + done, 2, True)
+            tq, tk, tv = (U.to_device([h[i] for h in data], torch, dev) for i in range(3))
+            binding.set_flash_variant(variant)
+            got = U.from_device(binding.attention(tq, tk, tv, T, Hs, Ws, iters, rec))
+            for h in range(2):
+                q64, k64, v64 = (U.to_f64(x) for x in data[h])
+                res = O.monarch_attention(q64, k64, v64, T, b, iters, recompute=(rec == 1), sink_average=(rec == 2),
+                                          keep_factors=True)
+                ref = res["O"].reshape(T * b, d)
+                rel, mx = U.rel_l2(got[h], ref), U.max_abs(got[h], ref)
+                what = f"T={T} Hs={Hs} Ws={Ws} d={d} sweeps={iters} recompute={rec} variant={variant}"
+                print(f"random configuration {what}: rel {rel:.2e} max {mx:.2e}")
+                assert np.isfinite(got[h]).all() and rel <= U.BF16_REL_L2, what
+                if rec == 2:
+                    # averaged with exact attention over the first frame: half of each part's error
+                    assert mx <= U.BF16_MAX_ABS, what
+                else:
+                    # element-wise: the flat 2e-2 where the first-order bound of the three bf16 roundings of an output
+                    # (y stored, L as an operand, O stored) and of alpha_L's own storage is smaller, that bound elsewhere
+                    ok, ratio = U.within_end_to_end_bound(got[h], res, U.BF16_MAX_ABS, True,
+                                                          (q64 / math.sqrt(d)).reshape(T, b, d), recomputed_frame=(rec == 1))
+                    assert ok, (what, ratio)
+            done += 1
+    finally:
+        binding.set_flash_variant(default)
+
+
 @pytest.mark.parametrize("T,Hs,Ws,d,dt,iters,rec", E2E)
 def test_attention_matches_oracle(env, T, Hs, Ws, d, dt, iters, rec):
     torch, binding, dev = env

@@ -24,35 +24,6 @@ def _tol(bf16):
     return (U.BF16_REL_L2, U.BF16_MAX_ABS) if bf16 else (1e-4, 1e-4)
 
 
-def _within(got, res, abs_tol, bf16, q_scaled=None, recomputed_frame=True):
-    """Element-wise bound against an oracle result `res` (kept factors).  In the bf16 path an output element
-    O[j,i] = sum_k L[j,k] y[k] carries three roundings: of every y[k] when it is stored (half an ulp, at most
-    2^-8 |y[k]|), of every weight L[j,k] as a matrix operand (2^-9 relative) and of the result (at most 2^-8 |O|):
-    (2^-8 + 2^-9) sum_k L[j,k] |y[k]| + 2^-8 |O|.  The weights themselves inherit the bf16 storage of alpha_L:
-    the temporal logit u[j,k] = Q[j] . alpha_L[k] moves by about 2^-9 (sum_v (Q[j,v] alpha_L[k,v])^2)^(1/2) (one
-    independent rounding per channel, root sum of squares), a softmax weight by at most twice the largest such
-    shift of its row, and the output by that times sum_k L[j,k] |y[k]|.  The control variants sharpen the
-    temporal factor: rows of y reach the output undiluted and differences of large rows do not average out, so
-    these terms exceed the flat 2e-2 in places.  Frame 0 is recomputed from all keys and stays under the flat
-    tolerance."""
-    T, s_, d = res["O"].shape
-    ref = res["O"].reshape(T * s_, d)
-    if not bf16:
-        return U.max_abs(got, ref) <= abs_tol, U.max_abs(got, ref) / abs_tol
-    spread = np.einsum("ijk,ikv->jiv", res["L"], np.abs(res["y"]))                       # [j, i, v]
-    du = 2.0 ** -9 * np.sqrt(np.einsum("jiv,ikv->ijk", q_scaled ** 2, res["aL"] ** 2))     # [i, j, k]
-    shift = 2.0 * du.max(axis=2).T                                                       # [j, i]
-    bound = (2.0 ** -8 + 2.0 ** -9 + shift[:, :, None]) * spread + 2.0 ** -8 * np.abs(res["O"])
-    bound = np.maximum(abs_tol, bound).reshape(T * s_, d)
-    if recomputed_frame:
-        bound[:s_] = abs_tol
-    ratio = np.abs(got - ref) / bound
-    w = np.unravel_index(np.argmax(ratio), ratio.shape)
-    print(f"  worst element: token {w[0]} (frame {w[0] // s_}) channel {w[1]}: got {got[w]:.5f} ref {ref[w]:.5f} "
-          f"sum L|y| {spread.reshape(T * s_, d)[w]:.4f} logit shift {shift.reshape(-1)[w[0]]:.4f} bound {bound[w]:.4f}")
-    return float(ratio[w]) <= 1.0, float(ratio[w])
-
-
 SHAPES = [
     # T, Hs, Ws, d, dtype
     (4, 4, 4, 32, "f32"),
@@ -142,7 +113,7 @@ def test_manual_control_matches_oracle(env, T, Hs, Ws, d, dt, iters, cr_control,
                                   cl_control=cl_control, cl_value=cl_value, keep_factors=True)
         ref = res["O"].reshape(T * b, d)
         free = O.monarch_attention(q64, k64, v64, T, b, iters, recompute=True)["O"].reshape(T * b, d)
-        ok, ratio = _within(got[h], res, abs_tol, bf16, (q64 / math.sqrt(d)).reshape(T, b, d))
+        ok, ratio = U.within_end_to_end_bound(got[h], res, abs_tol, bf16, (q64 / math.sqrt(d)).reshape(T, b, d))
         print(f"control T={T} b={b} d={d} {dt} t={iters} cR{cr_control} cL{cl_control}: rel {U.rel_l2(got[h], ref):.2e} "
               f"max {U.max_abs(got[h], ref):.2e} worst/bound {ratio:.2f}; variant vs plain {U.rel_l2(ref, free):.2e}")
         assert U.rel_l2(got[h], ref) <= rel_tol and ok
@@ -201,7 +172,7 @@ def test_per_call_options_on_two_streams(env):
         qs = (q64 / math.sqrt(d)).reshape(T, b, d)
         for tag, got, res, rec in (("plain", got_a[h], res_a, True), ("controlled", got_b[h], res_b, False)):
             ref = res["O"].reshape(T * b, d)
-            ok, ratio = _within(got, res, U.BF16_MAX_ABS, True, qs, recomputed_frame=rec)
+            ok, ratio = U.within_end_to_end_bound(got, res, U.BF16_MAX_ABS, True, qs, recomputed_frame=rec)
             print(f"options {tag} head {h}: rel {U.rel_l2(got, ref):.2e} max {U.max_abs(got, ref):.2e} worst/bound {ratio:.2f}")
             assert U.rel_l2(got, ref) <= U.BF16_REL_L2 and ok
         assert U.rel_l2(res_a["O"], res_b["O"]) > 5e-2      # the two settings really differ

@@ -81,3 +81,32 @@ def from_device(t):
 def random_bits(rng, shape, scale, bf16):
     x = (scale * rng.standard_normal(shape)).astype(np.float32)
     return synth.f32_to_bf16_bits(x) if bf16 else x
+
+
+def within_end_to_end_bound(got, res, abs_tol, bf16, q_scaled=None, recomputed_frame=True):
+    """Element-wise bound against an oracle result `res` (kept factors).  In the bf16 path an output element
+    O[j,i] = sum_k L[j,k] y[k] carries three roundings: of every y[k] when it is stored (half an ulp, at most
+    2^-8 |y[k]|), of every weight L[j,k] as a matrix operand (2^-9 relative) and of the result (at most 2^-8 |O|):
+    (2^-8 + 2^-9) sum_k L[j,k] |y[k]| + 2^-8 |O|.  The weights themselves inherit the bf16 storage of alpha_L:
+    the temporal logit u[j,k] = Q[j] . alpha_L[k] moves by about 2^-9 (sum_v (Q[j,v] alpha_L[k,v])^2)^(1/2) (one
+    independent rounding per channel, root sum of squares), a softmax weight by at most twice the largest such
+    shift of its row, and the output by that times sum_k L[j,k] |y[k]|.  The control variants sharpen the
+    temporal factor: rows of y reach the output undiluted and differences of large rows do not average out, so
+    these terms exceed the flat 2e-2 in places.  Frame 0 is recomputed from all keys and stays under the flat
+    tolerance."""
+    T, s_, d = res["O"].shape
+    ref = res["O"].reshape(T * s_, d)
+    if not bf16:
+        return max_abs(got, ref) <= abs_tol, max_abs(got, ref) / abs_tol
+    spread = np.einsum("ijk,ikv->jiv", res["L"], np.abs(res["y"]))                       # [j, i, v]
+    du = 2.0 ** -9 * np.sqrt(np.einsum("jiv,ikv->ijk", q_scaled ** 2, res["aL"] ** 2))     # [i, j, k]
+    shift = 2.0 * du.max(axis=2).T                                                       # [j, i]
+    bound = (2.0 ** -8 + 2.0 ** -9 + shift[:, :, None]) * spread + 2.0 ** -8 * np.abs(res["O"])
+    bound = np.maximum(abs_tol, bound).reshape(T * s_, d)
+    if recomputed_frame:
+        bound[:s_] = abs_tol
+    ratio = np.abs(got - ref) / bound
+    w = np.unravel_index(np.argmax(ratio), ratio.shape)
+    print(f"  worst element: token {w[0]} (frame {w[0] // s_}) channel {w[1]}: got {got[w]:.5f} ref {ref[w]:.5f} "
+          f"sum L|y| {spread.reshape(T * s_, d)[w]:.4f} logit shift {shift.reshape(-1)[w[0]]:.4f} bound {bound[w]:.4f}")
+    return float(ratio[w]) <= 1.0, float(ratio[w])
